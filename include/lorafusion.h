@@ -1,0 +1,117 @@
+/*
+ * lorafusion.h - C ABI of the MI355X (gfx950) fused LoRA linear layer.
+ *
+ * The layer is the LoRA-adapted linear of the LoRAFusion paper, Section 2.1, Eq. 1
+ * (notation of its Table 1):
+ *
+ *     Y = X W + alpha * (dropout(X) A) B,        W frozen,
+ *
+ * and its backward pass (dX, dA, dB), executed as the paper's five fused operations
+ * (Section 5.1, "FusedLoRA Design"): (1) dropout + down-projection, (2) base GEMM + up-projection,
+ * (3) dS together with dB, (4) dA, (5) dX = base gradient GEMM + masked LoRA gradient; and the
+ * mixed-adapter form of the same operations (Section 5.1, "Extending to FusedMultiLoRA"), where
+ * contiguous row segments of a packed token batch belong to different adapters.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ * - All tensor pointers are DEVICE pointers to row-major, contiguous arrays, 16-byte aligned.
+ *   Arrays named "host" below are HOST pointers, read before the call returns.
+ * - lora_bf16 is a raw bfloat16 bit pattern.  Products accumulate in fp32; bf16 outputs are
+ *   rounded to nearest even.
+ * - Storage layouts are the transposes of the paper's math shapes (its Figure 10 holds the
+ *   weights transposed for the hardware layout):
+ *       X [M,K]   W [N,K]   A [r,K]   B [N,r]   Y,dY [M,N]   dX [M,K]   S_saved [M,r]
+ *       dA [r,K] fp32       dB [N,r] fp32       multi: A [G,r,K]  B [G,N,r]  dA [G,r,K]  dB [G,N,r]
+ * - `s` is the paper's alpha (already divided by the rank if the caller follows that custom).
+ * - Dropout is inverted dropout on the LoRA branch only.  keep(i,j) is a counter-based hash
+ *   of (seed, row i local to the adapter's segment, column j); p is quantised to T/65536 with
+ *   T = min(65535, floor(p*65536)) and survivors are scaled by q = 65536/(65536-T).  The mask is
+ *   never stored: forward and backward regenerate it from (seed, p), so the caller must pass
+ *   the same seed and p to both.
+ * - S_saved (M*r bf16) receives s*q*(mask.X)A in forward and must be handed back to backward.
+ * - Ownership: the caller owns every buffer.  No entry point allocates or frees device
+ *   memory, synchronises the device, or touches a stream other than `stream`; work is only
+ *   enqueued.  Inputs are never modified.
+ * - Supported sizes: M >= 0 (M == 0 is a no-op), K and N positive multiples of 64,
+ *   r in {16, 32, 64}, 1 <= G <= 64, M < 2^31.
+ * - Errors: every call returns a lora_status and enqueues nothing unless it returns LORA_OK.
+ */
+#ifndef LORAFUSION_H
+#define LORAFUSION_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LORA_OK = 0,
+    LORA_ERR_NULL = 1,        /* a required pointer is NULL */
+    LORA_ERR_SHAPE = 2,       /* negative size, or K/N == 0, or M >= 2^31 */
+    LORA_ERR_ALIGN = 3,       /* a device pointer is not 16-byte aligned */
+    LORA_ERR_PARAM = 4,       /* p outside [0,1), or p/s not finite */
+    LORA_ERR_SEGMENTS = 5,    /* offsets do not rise from 0 to M */
+    LORA_ERR_WORKSPACE = 6,   /* workspace smaller than lora_bwd_workspace_bytes() */
+    LORA_ERR_UNSUPPORTED = 7, /* K or N not a multiple of 64, r not in {16,32,64}, G > 64 */
+    LORA_ERR_HIP = 8          /* a kernel launch failed */
+} lora_status;
+
+typedef uint16_t lora_bf16;
+typedef void* lora_stream; /* hipStream_t; NULL = the default stream */
+
+/* Forward, one adapter: operations (1) and (2) of Section 5.1 on Eq. 1.
+ * Writes Y [M,N] and S_saved [M,r]. */
+lora_status lora_fwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                     int64_t M, int64_t K, int64_t N, int32_t r, float s, float p, uint64_t seed,
+                     lora_bf16* Y, lora_bf16* S_saved, lora_stream stream);
+
+/* Bytes of scratch the backward entry points need for these sizes (G = number of adapters).
+ * Returns 0 for unsupported sizes. */
+size_t lora_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N, int32_t r, int32_t G);
+
+/* Backward, one adapter: operations (3), (4), (5) of Section 5.1 (chain rule on Eq. 1):
+ *   dS = s dY B^T, dB = s S^T dY, dA = Xhat^T dS, dX = dY W^T + mask*q*(dS A^T).
+ * dX may be NULL (skip the input gradient).  accumulate == 0 overwrites dA and dB, != 0 adds to
+ * them.  workspace is device scratch of at least lora_bwd_workspace_bytes() bytes, 256-byte
+ * aligned; its contents are undefined afterwards. */
+lora_status lora_bwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                     const lora_bf16* S_saved, const lora_bf16* dY,
+                     int64_t M, int64_t K, int64_t N, int32_t r, float s, float p, uint64_t seed,
+                     lora_bf16* dX, float* dA, float* dB, int accumulate,
+                     void* workspace, size_t workspace_bytes, lora_stream stream);
+
+/* Forward on a packed mixed-adapter batch (Section 5.1, FusedMultiLoRA): rows
+ * [seg_offsets[g], seg_offsets[g+1]) use adapter g = (A[g], B[g], s[g], p[g], seeds[g]); the base
+ * product X W is shared.  seg_offsets (host, G+1 entries) must rise from 0 to M; empty
+ * segments are allowed.  The mask row index restarts at 0 in every segment, so the result equals
+ * per-segment lora_fwd calls. */
+lora_status multi_lora_fwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                           int64_t M, int64_t K, int64_t N, int32_t r, int32_t G,
+                           const int64_t* seg_offsets, const float* s, const float* p,
+                           const uint64_t* seeds,
+                           lora_bf16* Y, lora_bf16* S_saved, lora_stream stream);
+
+/* Backward on a packed mixed-adapter batch: gradients are routed to the adapter that owns each
+ * row segment.  An empty segment's dA[g], dB[g] are zero-filled (left untouched if accumulate). */
+lora_status multi_lora_bwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                           const lora_bf16* S_saved, const lora_bf16* dY,
+                           int64_t M, int64_t K, int64_t N, int32_t r, int32_t G,
+                           const int64_t* seg_offsets, const float* s, const float* p,
+                           const uint64_t* seeds,
+                           lora_bf16* dX, float* dA, float* dB, int accumulate,
+                           void* workspace, size_t workspace_bytes, lora_stream stream);
+
+/* Diagnostic: writes keep(i,j) (1 = kept, 0 = dropped) for rows 0..M-1 and columns 0..K-1 of one
+ * adapter into keep [M,K] (device, bytes).  Any M, K >= 0. */
+lora_status lora_debug_mask(int64_t M, int64_t K, float p, uint64_t seed, uint8_t* keep,
+                            lora_stream stream);
+
+const char* lora_status_string(lora_status st);
+int lora_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LORAFUSION_H */

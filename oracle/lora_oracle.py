@@ -140,18 +140,28 @@ def _dropout(X, p, seed):
     return Xhat, keep, q
 
 
-def lora_fwd(X, W, A, B, s, p, seed):
-    """Eq. 1.  X [M,K], W [N,K], A [r,K], B [N,r] -> (Y [M,N], S [M,r]) with S = Xhat A."""
+def lora_fwd(X, W, A, B, s, p, seed, rows=None):
+    """Eq. 1.  X [M,K], W [N,K], A [r,K], B [N,r] -> (Y [M,N], S [M,r]) with S = Xhat A.
+
+    rows (optional index array): evaluate Y for these rows only (Y becomes [len(rows), N]); used
+    to sample outputs of very large problems.  S is always complete.
+    """
     X, W, A, B = _f64(X), _f64(W), _f64(A), _f64(B)
     s = float(np.float32(s))
     Xhat, _, _ = _dropout(X, p, seed)
     S = Xhat @ A.T
-    Y = X @ W.T + s * (S @ B.T)
+    if rows is None:
+        Y = X @ W.T + s * (S @ B.T)
+    else:
+        Y = X[rows] @ W.T + s * (S[rows] @ B.T)
     return Y, S
 
 
-def lora_bwd(X, W, A, B, dY, s, p, seed):
-    """Chain rule on Eq. 1.  Returns (dX [M,K], dA [r,K], dB [N,r], dS [M,r])."""
+def lora_bwd(X, W, A, B, dY, s, p, seed, rows=None):
+    """Chain rule on Eq. 1.  Returns (dX [M,K], dA [r,K], dB [N,r], dS [M,r]).
+
+    rows (optional index array): evaluate dX for these rows only; dA, dB, dS are always complete.
+    """
     X, W, A, B, dY = _f64(X), _f64(W), _f64(A), _f64(B), _f64(dY)
     s = float(np.float32(s))
     Xhat, keep, q = _dropout(X, p, seed)
@@ -159,7 +169,10 @@ def lora_bwd(X, W, A, B, dY, s, p, seed):
     dS = s * (dY @ B)
     dB = s * (dY.T @ S)
     dA = dS.T @ Xhat
-    dX = dY @ W + np.where(keep, q * (dS @ A), 0.0)
+    if rows is None:
+        dX = dY @ W + np.where(keep, q * (dS @ A), 0.0)
+    else:
+        dX = dY[rows] @ W + np.where(keep[rows], q * (dS[rows] @ A), 0.0)
     return dX, dA, dB, dS
 
 
@@ -171,30 +184,51 @@ def _segments(seg_offsets, M):
     return o
 
 
-def multi_lora_fwd(X, W, A, B, seg_offsets, s, p, seeds):
-    """Packed batch: rows [o_g, o_{g+1}) use adapter g.  A [G,r,K], B [G,N,r]; s, p, seeds [G]."""
+def _rows_of_segment(rows, lo, hi):
+    """Positions in `rows` that fall in [lo, hi), and those rows relative to lo."""
+    rows = np.asarray(rows)
+    pos = np.nonzero((rows >= lo) & (rows < hi))[0]
+    return pos, rows[pos] - lo
+
+
+def multi_lora_fwd(X, W, A, B, seg_offsets, s, p, seeds, rows=None):
+    """Packed batch: rows [o_g, o_{g+1}) use adapter g.  A [G,r,K], B [G,N,r]; s, p, seeds [G].
+
+    rows: as in lora_fwd (global row indices); Y then has one line per listed row.
+    """
     X, W, A, B = _f64(X), _f64(W), _f64(A), _f64(B)
     o = _segments(seg_offsets, X.shape[0])
     G = len(o) - 1
-    Y = np.empty((X.shape[0], W.shape[0]))
+    Y = np.empty((X.shape[0] if rows is None else len(rows), W.shape[0]))
     S = np.empty((X.shape[0], A.shape[1]))
     for g in range(G):
-        Y[o[g]:o[g + 1]], S[o[g]:o[g + 1]] = lora_fwd(
-            X[o[g]:o[g + 1]], W, A[g], B[g], s[g], p[g], seeds[g])
+        sl = slice(o[g], o[g + 1])
+        if rows is None:
+            Y[sl], S[sl] = lora_fwd(X[sl], W, A[g], B[g], s[g], p[g], seeds[g])
+        else:
+            pos, local = _rows_of_segment(rows, o[g], o[g + 1])
+            Y[pos], S[sl] = lora_fwd(X[sl], W, A[g], B[g], s[g], p[g], seeds[g], rows=local)
     return Y, S
 
 
-def multi_lora_bwd(X, W, A, B, dY, seg_offsets, s, p, seeds):
-    """Returns (dX [M,K], dA [G,r,K], dB [G,N,r], dS [M,r]); an empty segment gets zero dA, dB."""
+def multi_lora_bwd(X, W, A, B, dY, seg_offsets, s, p, seeds, rows=None):
+    """Returns (dX [M,K], dA [G,r,K], dB [G,N,r], dS [M,r]); an empty segment gets zero dA, dB.
+
+    rows: as in lora_bwd (global row indices); dX then has one line per listed row.
+    """
     X, W, A, B, dY = _f64(X), _f64(W), _f64(A), _f64(B), _f64(dY)
     o = _segments(seg_offsets, X.shape[0])
     G = len(o) - 1
-    dX = np.empty_like(X)
+    dX = np.empty((X.shape[0] if rows is None else len(rows), X.shape[1]))
     dA = np.zeros_like(A)
     dB = np.zeros_like(B)
     dS = np.empty((X.shape[0], A.shape[1]))
     for g in range(G):
         sl = slice(o[g], o[g + 1])
-        dX[sl], dA[g], dB[g], dS[sl] = lora_bwd(
-            X[sl], W, A[g], B[g], dY[sl], s[g], p[g], seeds[g])
+        if rows is None:
+            dX[sl], dA[g], dB[g], dS[sl] = lora_bwd(X[sl], W, A[g], B[g], dY[sl], s[g], p[g], seeds[g])
+        else:
+            pos, local = _rows_of_segment(rows, o[g], o[g + 1])
+            dX[pos], dA[g], dB[g], dS[sl] = lora_bwd(X[sl], W, A[g], B[g], dY[sl], s[g], p[g], seeds[g],
+                                                      rows=local)
     return dX, dA, dB, dS

@@ -1,0 +1,194 @@
+// C ABI of the fused LoRA linear layer: argument validation, the per-adapter lookup table,
+// workspace carving and the launch sequences of the five fused operations (Section 5.1).
+// Nothing here allocates device memory or synchronises; every kernel goes to the caller's stream.
+#include <math.h>
+#include <string.h>
+
+#include "../../include/lorafusion.h"
+#include "lf_internal.h"
+
+using namespace lf;
+
+namespace {
+
+inline bool misaligned(const void* p, size_t a = 16) { return ((uintptr_t)p & (a - 1)) != 0; }
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+lora_status check_shape(int64_t M, int64_t K, int64_t N, int32_t r, int32_t G) {
+    if (M < 0 || K <= 0 || N <= 0 || M >= (1ll << 31) || K >= (1ll << 31) || N >= (1ll << 31)) return LORA_ERR_SHAPE;
+    if (G < 1) return LORA_ERR_SHAPE;
+    if ((K & 63) || (N & 63) || !(r == 16 || r == 32 || r == 64) || G > kMaxAdapters) return LORA_ERR_UNSUPPORTED;
+    return LORA_OK;
+}
+
+// Threshold and keys exactly as the written specification of the hash: p is an IEEE float
+// widened to double, T = min(65535, floor(p * 65536)); k0 = mix(seed_lo ^ C5), k1 = mix(seed_hi + k0).
+lora_status fill_adapter(AdapterTable& tb, int g, float s, float p, uint64_t seed) {
+    if (!(p >= 0.0f && p < 1.0f) || !isfinite(s)) return LORA_ERR_PARAM;
+    double t = floor((double)p * 65536.0);
+    uint32_t T = t > 65535.0 ? 65535u : (uint32_t)t;
+    tb.T[g] = T;
+    tb.q[g] = (float)(65536.0 / (65536.0 - (double)T));
+    tb.s[g] = s;
+    tb.k0[g] = mix32((uint32_t)(seed & 0xFFFFFFFFull) ^ kC5);
+    tb.k1[g] = mix32((uint32_t)(seed >> 32) + tb.k0[g]);
+    return LORA_OK;
+}
+
+lora_status build_table(AdapterTable& tb, int64_t M, int32_t G, const int64_t* off, const float* s,
+                        const float* p, const uint64_t* seeds) {
+    memset(&tb, 0, sizeof(tb));
+    tb.G = G;
+    if (off[0] != 0 || off[G] != M) return LORA_ERR_SEGMENTS;
+    for (int g = 0; g < G; ++g)
+        if (off[g + 1] < off[g]) return LORA_ERR_SEGMENTS;
+    for (int g = 0; g <= G; ++g) tb.row0[g] = (int)off[g];
+    for (int g = 0; g < G; ++g) {
+        lora_status st = fill_adapter(tb, g, s[g], p[g], seeds[g]);
+        if (st != LORA_OK) return st;
+    }
+    return LORA_OK;
+}
+
+struct Workspace {
+    lora_bf16* dS; float* part_ds; float* part_db; float* part_da; size_t bytes;
+};
+
+Workspace carve(void* base, int64_t M, int64_t K, int64_t N, int32_t r, int32_t G) {
+    const int64_t tiles = M / kRowTile + G;                      // upper bound on row tiles
+    const int64_t chunks = (N + kStreamChunk - 1) / kStreamChunk;
+    size_t off = 0;
+    Workspace w;
+    char* b = (char*)base;
+    w.dS = (lora_bf16*)(b + off);      off += align_up((size_t)M * r * 2);
+    w.part_ds = (float*)(b + off);     off += align_up((size_t)chunks * M * r * 4);
+    w.part_db = (float*)(b + off);     off += align_up((size_t)tiles * N * r * 4);
+    w.part_da = (float*)(b + off);     off += align_up((size_t)tiles * r * K * 4);
+    w.bytes = off;
+    return w;
+}
+
+lora_status fwd_impl(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                     int64_t M, int64_t K, int64_t N, int32_t r, const AdapterTable& tb,
+                     lora_bf16* Y, lora_bf16* S, hipStream_t st) {
+    DownArgs d{X, A, S, (int)M, (int)K, r, tb};
+    if (launch_down(d, st) != hipSuccess) return LORA_ERR_HIP;
+    FwdGemmArgs f{X, W, S, B, Y, (int)M, (int)K, (int)N, r, 0, 0, tb};
+    if (launch_fwd_gemm(f, st) != hipSuccess) return LORA_ERR_HIP;
+    return LORA_OK;
+}
+
+lora_status bwd_impl(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                     const lora_bf16* S, const lora_bf16* dY, int64_t M, int64_t K, int64_t N, int32_t r,
+                     const AdapterTable& tb, lora_bf16* dX, float* dA, float* dB, int accumulate,
+                     void* workspace, hipStream_t st) {
+    const Workspace ws = carve(workspace, M, K, N, r, tb.G);
+    const int chunks = (int)((N + kStreamChunk - 1) / kStreamChunk);
+    StreamArgs s3{dY, S, B, ws.part_db, ws.part_ds, (int)M, (int)N, r, 0, 0, tb};
+    if (launch_stream_dsdb(s3, st) != hipSuccess) return LORA_ERR_HIP;
+    FinalizeArgs fin{ws.part_ds, ws.dS, ws.part_db, dB, ws.part_da, dA,
+                     (int)M, (int)K, (int)N, r, chunks, accumulate, tb};
+    if (launch_finalize_ds_db(fin, st) != hipSuccess) return LORA_ERR_HIP;
+    StreamArgs s4{X, ws.dS, nullptr, ws.part_da, nullptr, (int)M, (int)K, r, 0, 0, tb};
+    if (launch_stream_da(s4, st) != hipSuccess) return LORA_ERR_HIP;
+    if (launch_finalize_da(fin, st) != hipSuccess) return LORA_ERR_HIP;
+    if (dX) {
+        DxGemmArgs g5{dY, W, ws.dS, A, dX, (int)M, (int)K, (int)N, r, 0, 0, tb};
+        if (launch_bwd_dx(g5, st) != hipSuccess) return LORA_ERR_HIP;
+    }
+    return LORA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lora_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N, int32_t r, int32_t G) {
+    if (check_shape(M, K, N, r, G) != LORA_OK) return 0;
+    return carve(nullptr, M, K, N, r, G).bytes;
+}
+
+lora_status multi_lora_fwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                           int64_t M, int64_t K, int64_t N, int32_t r, int32_t G,
+                           const int64_t* seg_offsets, const float* s, const float* p, const uint64_t* seeds,
+                           lora_bf16* Y, lora_bf16* S_saved, lora_stream stream) {
+    if (!X || !W || !A || !B || !Y || !S_saved || !seg_offsets || !s || !p || !seeds) return LORA_ERR_NULL;
+    lora_status st = check_shape(M, K, N, r, G);
+    if (st != LORA_OK) return st;
+    if (misaligned(X) || misaligned(W) || misaligned(A) || misaligned(B) || misaligned(Y) || misaligned(S_saved))
+        return LORA_ERR_ALIGN;
+    AdapterTable tb;
+    st = build_table(tb, M, G, seg_offsets, s, p, seeds);
+    if (st != LORA_OK) return st;
+    if (M == 0) return LORA_OK;
+    return fwd_impl(X, W, A, B, M, K, N, r, tb, Y, S_saved, (hipStream_t)stream);
+}
+
+lora_status lora_fwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                     int64_t M, int64_t K, int64_t N, int32_t r, float s, float p, uint64_t seed,
+                     lora_bf16* Y, lora_bf16* S_saved, lora_stream stream) {
+    const int64_t off[2] = {0, M};
+    return multi_lora_fwd(X, W, A, B, M, K, N, r, 1, off, &s, &p, &seed, Y, S_saved, stream);
+}
+
+lora_status multi_lora_bwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                           const lora_bf16* S_saved, const lora_bf16* dY,
+                           int64_t M, int64_t K, int64_t N, int32_t r, int32_t G,
+                           const int64_t* seg_offsets, const float* s, const float* p, const uint64_t* seeds,
+                           lora_bf16* dX, float* dA, float* dB, int accumulate,
+                           void* workspace, size_t workspace_bytes, lora_stream stream) {
+    if (!X || !W || !A || !B || !S_saved || !dY || !dA || !dB || !workspace || !seg_offsets || !s || !p || !seeds)
+        return LORA_ERR_NULL;
+    lora_status st = check_shape(M, K, N, r, G);
+    if (st != LORA_OK) return st;
+    if (misaligned(X) || misaligned(W) || misaligned(A) || misaligned(B) || misaligned(S_saved) ||
+        misaligned(dY) || misaligned(dA) || misaligned(dB) || (dX && misaligned(dX)) || misaligned(workspace, 256))
+        return LORA_ERR_ALIGN;
+    AdapterTable tb;
+    st = build_table(tb, M, G, seg_offsets, s, p, seeds);
+    if (st != LORA_OK) return st;
+    if (workspace_bytes < carve(nullptr, M, K, N, r, G).bytes) return LORA_ERR_WORKSPACE;
+    return bwd_impl(X, W, A, B, S_saved, dY, M, K, N, r, tb, dX, dA, dB, accumulate, workspace,
+                    (hipStream_t)stream);
+}
+
+lora_status lora_bwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                     const lora_bf16* S_saved, const lora_bf16* dY,
+                     int64_t M, int64_t K, int64_t N, int32_t r, float s, float p, uint64_t seed,
+                     lora_bf16* dX, float* dA, float* dB, int accumulate,
+                     void* workspace, size_t workspace_bytes, lora_stream stream) {
+    const int64_t off[2] = {0, M};
+    return multi_lora_bwd(X, W, A, B, S_saved, dY, M, K, N, r, 1, off, &s, &p, &seed, dX, dA, dB, accumulate,
+                          workspace, workspace_bytes, stream);
+}
+
+lora_status lora_debug_mask(int64_t M, int64_t K, float p, uint64_t seed, uint8_t* keep, lora_stream stream) {
+    if (M < 0 || K < 0 || M >= (1ll << 31) || K >= (1ll << 31)) return LORA_ERR_SHAPE;
+    AdapterTable tb;
+    lora_status st = fill_adapter(tb, 0, 1.0f, p, seed);
+    if (st != LORA_OK) return st;
+    if (M == 0 || K == 0) return LORA_OK;
+    if (!keep) return LORA_ERR_NULL;
+    if (launch_debug_mask(M, K, tb.T[0], tb.k0[0], tb.k1[0], keep, (hipStream_t)stream) != hipSuccess)
+        return LORA_ERR_HIP;
+    return LORA_OK;
+}
+
+const char* lora_status_string(lora_status st) {
+    switch (st) {
+        case LORA_OK: return "ok";
+        case LORA_ERR_NULL: return "a required pointer is NULL";
+        case LORA_ERR_SHAPE: return "invalid shape";
+        case LORA_ERR_ALIGN: return "pointer not sufficiently aligned";
+        case LORA_ERR_PARAM: return "dropout probability outside [0,1) or non-finite scale";
+        case LORA_ERR_SEGMENTS: return "segment offsets must rise from 0 to M";
+        case LORA_ERR_WORKSPACE: return "workspace too small";
+        case LORA_ERR_UNSUPPORTED: return "unsupported size (K, N multiples of 64; r in {16,32,64}; G <= 64)";
+        case LORA_ERR_HIP: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+int lora_version(void) { return 100; }
+
+}  // extern "C"

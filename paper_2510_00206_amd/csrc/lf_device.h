@@ -1,0 +1,139 @@
+// Device-side helpers shared by the gfx950 kernels: vector types, the dropout hash, LDS swizzles,
+// and the per-adapter table that routes row tiles to adapters (Section 5.1, FusedMultiLoRA:
+// every M-tile carries an adapter id that indexes a small lookup table).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lf {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kMaxAdapters = 64;
+
+// Lookup table passed by value in the kernel arguments.
+struct AdapterTable {
+    int G;
+    int row0[kMaxAdapters + 1];   // segment g owns rows [row0[g], row0[g+1])
+    uint32_t T[kMaxAdapters];     // dropout threshold: keep iff bits16 >= T
+    uint32_t k0[kMaxAdapters];    // seed-derived hash keys
+    uint32_t k1[kMaxAdapters];
+    float s[kMaxAdapters];        // the paper's alpha
+    float q[kMaxAdapters];        // survivor scale 65536/(65536-T)
+};
+
+// A row tile: `rows` valid rows starting at global row `row_start`, owned by adapter g.
+struct RowTile {
+    int g, row_start, rows, local_row0;   // local_row0 = row_start - row0[g] (mask row index base)
+};
+
+// Tiles never straddle a segment: segment g contributes ceil(len/gran) tiles.
+__device__ __forceinline__ bool find_row_tile(const AdapterTable& tb, int gran, int tile, RowTile& rt) {
+    int t = tile;
+    for (int g = 0; g < tb.G; ++g) {
+        const int lo = tb.row0[g], hi = tb.row0[g + 1];
+        const int nt = (hi - lo + gran - 1) / gran;
+        if (t < nt) {
+            rt.g = g;
+            rt.row_start = lo + t * gran;
+            rt.rows = min(gran, hi - rt.row_start);
+            rt.local_row0 = t * gran;
+            return true;
+        }
+        t -= nt;
+    }
+    return false;
+}
+
+// ---- dropout hash (unsigned 32-bit arithmetic) ------------------------------------------------
+constexpr uint32_t kGold = 0x9E3779B9u, kM1 = 0x6A09E667u, kM2 = 0xBB67AE85u, kC5 = 0x3C6EF373u,
+                   kC7 = 0xA54FF53Bu;
+
+__host__ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
+    x ^= x >> 16; x *= kM1; x ^= x >> 15; x *= kM2; x ^= x >> 16;
+    return x;
+}
+
+struct RowKey { uint32_t a, b; };
+
+__device__ __forceinline__ RowKey row_key(uint32_t k0, uint32_t k1, uint32_t local_row) {
+    RowKey rk;
+    rk.a = mix32(k1 ^ (local_row * kGold));
+    rk.b = mix32(rk.a + k0 + kC7);
+    return rk;
+}
+
+// One word decides columns 2*cp (low half) and 2*cp+1 (high half).
+__device__ __forceinline__ uint32_t hash_word(RowKey rk, uint32_t cp) {
+    uint32_t x = rk.a + cp * kGold;
+    x ^= x >> 16; x *= kM1; x += rk.b; x ^= x >> 15; x *= kM2; x ^= x >> 16;
+    return x;
+}
+
+// AND-mask for a packed pair of bf16 (even column in the low half).
+__device__ __forceinline__ uint32_t keep_pair_mask(uint32_t w, uint32_t T) {
+    return ((w & 0xFFFFu) >= T ? 0x0000FFFFu : 0u) | ((w >> 16) >= T ? 0xFFFF0000u : 0u);
+}
+
+// Mask 8 consecutive bf16 (columns col..col+7, col % 8 == 0) held in a 16-byte vector.
+__device__ __forceinline__ u32x4 mask8(u32x4 v, RowKey rk, uint32_t col, uint32_t T) {
+    const uint32_t cp = col >> 1;
+    v.x &= keep_pair_mask(hash_word(rk, cp + 0), T);
+    v.y &= keep_pair_mask(hash_word(rk, cp + 1), T);
+    v.z &= keep_pair_mask(hash_word(rk, cp + 2), T);
+    v.w &= keep_pair_mask(hash_word(rk, cp + 3), T);
+    return v;
+}
+
+// ---- bf16 helpers -----------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    bf16x2 v;
+    v.x = (__bf16)lo;
+    v.y = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// ---- LDS layouts --------------------------------------------------------------------------------
+// Tiles are stored as rows of 16-byte chunks.  The chunk index is XOR-ed with a function of the
+// row so that (a) eight consecutive rows read at one chunk index (row-operand reads, 16 B per
+// lane) and (b) four consecutive rows read over 32 contiguous bytes (transposing reads, 8 B per
+// lane) both spread over all banks.
+__device__ __forceinline__ int swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+
+// Byte offset of 16-byte chunk `chunk` of row `row` in a tile whose rows hold `nchunk` chunks
+// (nchunk a power of two).
+__device__ __forceinline__ int tile_off(int row, int chunk, int nchunk) {
+    return (row * nchunk + (chunk ^ (swz(row) & (nchunk - 1)))) * 16;
+}
+
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+// Transposing LDS read: the 16 lanes of a group address a 4-row x 16-column block of 16-bit
+// elements (lane i: row i/4, columns 4*(i%4)..+3); lane i receives column i of the four rows.
+__device__ __forceinline__ s16x4 lds_read_tr(const char* lds_base, int byte_off) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_s16x4*)(__attribute__((address_space(3))) char*)(lds_base + byte_off));
+}
+
+// Byte offset for the transposing read of rows r0..r0+3 (r0 % 4 == 0), columns c0..c0+15
+// (c0 % 16 == 0), for lane-in-group i16, in a swizzled tile with nchunk chunks per row.
+__device__ __forceinline__ int tr_off(int r0, int c0, int i16, int nchunk) {
+    const int row = r0 + (i16 >> 2);
+    const int col = c0 + ((i16 & 3) << 2);           // element column, multiple of 4
+    return tile_off(row, col >> 3, nchunk) + ((col & 7) << 1);
+}
+
+__device__ __forceinline__ bf16x8 join_tr(s16x4 lo, s16x4 hi) {
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+}  // namespace lf

@@ -1,0 +1,68 @@
+// Internal C++ interface between the C ABI (lf_api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "lf_device.h"
+
+typedef uint16_t lora_bf16;
+
+namespace lf {
+
+// Operation (1): S' = s*q*(mask.X) A^T.
+struct DownArgs {
+    const lora_bf16* X; const lora_bf16* A; lora_bf16* S;
+    int M, K, r;
+    AdapterTable tb;
+};
+
+// Operation (2).
+struct FwdGemmArgs {
+    const lora_bf16* X; const lora_bf16* W; const lora_bf16* S; const lora_bf16* B; lora_bf16* Y;
+    int M, K, N, r, tiles_m, tiles_n;
+    AdapterTable tb;
+};
+
+// Operations (3) and (4) share one streaming kernel (see lf_stream.hip).
+struct StreamArgs {
+    const lora_bf16* big;      // dY [M,N] for (3), X [M,K] for (4)
+    const lora_bf16* small_;   // S' [M,r] for (3), dS [M,r] for (4)
+    const lora_bf16* Bmat;     // B [G,N,r] for (3), unused for (4)
+    float* part_out;           // per-row-tile partials of dB ([tiles,N,r]) or dA ([tiles,r,K])
+    float* part_ds;            // (3): per-column-chunk partials of dS [chunks,M,r]
+    int M, C, r;               // C = N for (3), K for (4)
+    int tiles_m, chunks;
+    AdapterTable tb;
+};
+
+// Reductions of the partials.
+struct FinalizeArgs {
+    const float* part_ds; lora_bf16* dS;        // dS[i,c] = s_g * sum over chunks
+    const float* part_db; float* dB;            // dB[g,n,c] (+)= sum over the row tiles of segment g
+    const float* part_da; float* dA;            // dA[g,c,j] (+)= q_g * sum over the row tiles of segment g
+    int M, K, N, r, chunks, accumulate;
+    AdapterTable tb;
+};
+
+// Operation (5).
+struct DxGemmArgs {
+    const lora_bf16* dY; const lora_bf16* W; const lora_bf16* dS; const lora_bf16* A; lora_bf16* dX;
+    int M, K, N, r, tiles_m, tiles_n;
+    AdapterTable tb;
+};
+
+constexpr int kRowTile = 256;        // row-tile granularity of the GEMMs and of the dA/dB partials
+constexpr int kStreamChunk = 512;    // column-chunk width of the streaming kernel
+
+hipError_t launch_down(const DownArgs& a, hipStream_t st);
+hipError_t launch_fwd_gemm(FwdGemmArgs a, hipStream_t st);
+hipError_t launch_stream_dsdb(StreamArgs a, hipStream_t st);
+hipError_t launch_stream_da(StreamArgs a, hipStream_t st);
+hipError_t launch_finalize_ds_db(const FinalizeArgs& a, hipStream_t st);
+hipError_t launch_finalize_da(const FinalizeArgs& a, hipStream_t st);
+hipError_t launch_bwd_dx(DxGemmArgs a, hipStream_t st);
+hipError_t launch_debug_mask(int64_t M, int64_t K, uint32_t T, uint32_t k0, uint32_t k1, uint8_t* keep,
+                             hipStream_t st);
+
+}  // namespace lf

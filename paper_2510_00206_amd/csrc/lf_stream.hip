@@ -1,0 +1,288 @@
+// The two bandwidth-bound backward operations of the fused LoRA linear layer (Section 5.1,
+// FusedLoRA Design), as one streaming kernel template over a big [M,C] activation:
+//   operation (3), big = dY [M,N]:  dS[i,c] = s sum_n dY[i,n] B[n,c]   and   dB[n,c] = sum_i dY[i,n] S'[i,c]
+//                                   (both from a single read of dY)
+//   operation (4), big = X  [M,K]:  dA[c,j] = q sum_i keep(i,j) X[i,j] dS[i,c]   (mask regenerated)
+// A workgroup owns a (256-row tile) x (512-column chunk) panel of `big`, walks it in 64-row steps
+// through LDS and reduces over its rows with 16x16x32 bf16 MFMAs whose row-contracted operand is
+// fetched with transposing LDS reads.  Results are partial sums (dB/dA per row tile, dS per column
+// chunk) that the finalize kernels add in a fixed order, so repeated runs agree bit for bit.
+#include "lf_device.h"
+#include "lf_internal.h"
+
+namespace lf {
+
+constexpr int ST_THREADS = 512;
+constexpr int ST_STEP = 64;                        // rows per step
+constexpr int ST_CH16 = kStreamChunk / 8;          // 16-byte chunks per panel row: 64
+constexpr int ST_BIG_BYTES = ST_STEP * kStreamChunk * 2;   // 64 KB
+
+#define LF_MFMA16(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_bf16((a), (b), (c), 0, 0, 0)
+
+__device__ __forceinline__ bf16x8 read_tr_frag(const char* lds, int r0, int c0, int nchunk) {
+    const int l = threadIdx.x & 63;
+    const s16x4 lo = lds_read_tr(lds, tr_off(r0, c0, l & 15, nchunk));
+    const s16x4 hi = lds_read_tr(lds, tr_off(r0 + 4, c0, l & 15, nchunk));
+    return join_tr(lo, hi);
+}
+
+template <int CB, bool IS_DA>   // CB = r/16; IS_DA: operation (4), else operation (3)
+__global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int R = CB * 16, RCH = CB * 2;                  // rank, 16-byte chunks per small row
+    char* lds_big = smem;                                     // [64][64 chunks]
+    char* lds_small = lds_big + ST_BIG_BYTES;                 // [64][RCH chunks]
+    char* lds_b = lds_small + ST_STEP * R * 2;                // (3): B chunk [512][RCH chunks]
+    char* lds_red = lds_b + (IS_DA ? 0 : kStreamChunk * R * 2);   // (3): [4][CB][64] f32x4
+
+    const int tile = blockIdx.x / p.chunks, chunk_id = blockIdx.x - tile * p.chunks;
+    RowTile rt;
+    if (!find_row_tile(p.tb, kRowTile, tile, rt)) return;
+    const int c0 = chunk_id * kStreamChunk;
+    const int cols_valid = min(kStreamChunk, p.C - c0);       // multiple of 64
+    const int t = threadIdx.x, l = t & 63, w = t >> 6;
+    const int g = rt.g;
+    const uint32_t T = p.tb.T[g], hk0 = p.tb.k0[g], hk1 = p.tb.k1[g];
+
+    if (!IS_DA) {
+        // B chunk [cols_valid, r] of adapter g -> LDS once (rows past the end are zero)
+        const lora_bf16* Bg = p.Bmat + ((int64_t)g * p.C + c0) * R;
+        for (int idx = t; idx < kStreamChunk * RCH; idx += ST_THREADS) {
+            const int row = idx / RCH, ch = idx - row * RCH;
+            u32x4 v = u32x4{0u, 0u, 0u, 0u};
+            if (row < cols_valid) v = *(const u32x4*)(Bg + (int64_t)row * R + ch * 8);
+            *(u32x4*)(lds_b + tile_off(row, ch, RCH)) = v;
+        }
+    }
+
+    f32x4 acc[4][CB];
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) acc[jb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const lora_bf16* big = p.big + (int64_t)rt.row_start * p.C + c0;
+    const lora_bf16* small_ = p.small_ + (int64_t)rt.row_start * R;
+    const int nsteps = (rt.rows + ST_STEP - 1) / ST_STEP;
+    const int bchunk = t & 63;                                // this thread's 16-byte chunk of a panel row
+    const bool col_ok = bchunk * 8 < cols_valid;
+
+    u32x4 rb_[8], rs_;
+    auto load_step = [&](int step) {
+        const int rows_left = rt.rows - step * ST_STEP;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = (t >> 6) + 8 * i;
+            rb_[i] = u32x4{0u, 0u, 0u, 0u};
+            if (col_ok && row < rows_left)
+                rb_[i] = *(const u32x4*)(big + (int64_t)(step * ST_STEP + row) * p.C + bchunk * 8);
+        }
+        rs_ = u32x4{0u, 0u, 0u, 0u};
+        if (t < ST_STEP * RCH) {
+            const int row = t / RCH, ch = t - row * RCH;
+            if (row < rows_left) rs_ = *(const u32x4*)(small_ + (int64_t)(step * ST_STEP + row) * R + ch * 8);
+        }
+    };
+    auto store_step = [&](int step) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = (t >> 6) + 8 * i;
+            u32x4 v = rb_[i];
+            if (IS_DA) {
+                const RowKey rk = row_key(hk0, hk1, (uint32_t)(rt.local_row0 + step * ST_STEP + row));
+                v = mask8(v, rk, (uint32_t)(c0 + bchunk * 8), T);
+            }
+            *(u32x4*)(lds_big + tile_off(row, bchunk, ST_CH16)) = v;
+        }
+        if (t < ST_STEP * RCH) {
+            const int row = t / RCH, ch = t - row * RCH;
+            *(u32x4*)(lds_small + tile_off(row, ch, RCH)) = rs_;
+        }
+    };
+
+    load_step(0);
+    for (int step = 0; step < nsteps; ++step) {
+        store_step(step);
+        __syncthreads();
+        if (step + 1 < nsteps) load_step(step + 1);
+
+        // reduction over the step's 64 rows: this wave owns panel columns [64w, 64w+64)
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const int r0 = kk * 32 + 8 * (l >> 4);
+            bf16x8 fs[CB];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) fs[cb] = read_tr_frag(lds_small, r0, cb * 16, RCH);
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb) {
+                const bf16x8 fb = read_tr_frag(lds_big, r0, w * 64 + jb * 16, ST_CH16);
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    acc[jb][cb] = IS_DA ? LF_MFMA16(fb, fs[cb], acc[jb][cb])     // D[j][c]
+                                        : LF_MFMA16(fs[cb], fb, acc[jb][cb]);    // D[c][n]
+            }
+        }
+
+        if (!IS_DA) {
+            // dS for the step's rows over this panel's columns: wave = (16-row block, column half)
+            const int rb = w & 3, kh = w >> 2;
+            f32x4 ads[CB];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) ads[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kq = 0; kq < 8; ++kq) {
+                const int ncol = kh * 256 + kq * 32;              // panel column of this k-chunk
+                const u32x4 tv = *(const u32x4*)(lds_big + tile_off(rb * 16 + (l & 15), (ncol >> 3) + (l >> 4), ST_CH16));
+                const bf16x8 ft = __builtin_bit_cast(bf16x8, tv);
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    const bf16x8 fbm = read_tr_frag(lds_b, ncol + 8 * (l >> 4), cb * 16, RCH);
+                    ads[cb] = LF_MFMA16(fbm, ft, ads[cb]);         // D[c][i]
+                }
+            }
+            f32x4* red = (f32x4*)lds_red;
+            if (kh == 1) {
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) red[(rb * CB + cb) * 64 + l] = ads[cb];
+            }
+            __syncthreads();
+            if (kh == 0) {
+                const int row = step * ST_STEP + rb * 16 + (l & 15);
+                if (row < rt.rows) {
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb) {
+                        const f32x4 v = ads[cb] + red[(rb * CB + cb) * 64 + l];
+                        *(f32x4*)(p.part_ds + ((int64_t)chunk_id * p.M + rt.row_start + row) * R + cb * 16 + 4 * (l >> 4)) = v;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // partial dB [tile][n][c] or dA [tile][c][j] of this panel
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+        const int colb = w * 64 + jb * 16;
+        if (colb >= cols_valid) continue;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            if (IS_DA) {
+                const int c = cb * 16 + (l & 15), j = c0 + colb + 4 * (l >> 4);
+                *(f32x4*)(p.part_out + ((int64_t)tile * R + c) * p.C + j) = acc[jb][cb];
+            } else {
+                const int n = c0 + colb + (l & 15), c = cb * 16 + 4 * (l >> 4);
+                *(f32x4*)(p.part_out + ((int64_t)tile * p.C + n) * R + c) = acc[jb][cb];
+            }
+        }
+    }
+}
+
+static int count_tiles(const AdapterTable& tb, int gran) {
+    int n = 0;
+    for (int g = 0; g < tb.G; ++g) n += (tb.row0[g + 1] - tb.row0[g] + gran - 1) / gran;
+    return n;
+}
+
+template <int CB, bool IS_DA>
+static hipError_t launch_stream_t(StreamArgs a, hipStream_t st) {
+    constexpr int R = CB * 16;
+    const int lds = ST_BIG_BYTES + ST_STEP * R * 2 + (IS_DA ? 0 : kStreamChunk * R * 2 + 4 * CB * 64 * 16);
+    a.tiles_m = count_tiles(a.tb, kRowTile);
+    a.chunks = (a.C + kStreamChunk - 1) / kStreamChunk;
+    if (a.tiles_m == 0) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute((const void*)stream_kernel<CB, IS_DA>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((stream_kernel<CB, IS_DA>), dim3(a.tiles_m * a.chunks), dim3(ST_THREADS), lds, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_stream_dsdb(StreamArgs a, hipStream_t st) {
+    switch (a.r) {
+        case 16: return launch_stream_t<1, false>(a, st);
+        case 32: return launch_stream_t<2, false>(a, st);
+        case 64: return launch_stream_t<4, false>(a, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_stream_da(StreamArgs a, hipStream_t st) {
+    switch (a.r) {
+        case 16: return launch_stream_t<1, true>(a, st);
+        case 32: return launch_stream_t<2, true>(a, st);
+        case 64: return launch_stream_t<4, true>(a, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+// ---- finalize: fixed-order sums of the partials ---------------------------------------------------
+__device__ __forceinline__ int segment_of_row(const AdapterTable& tb, int row) {
+    int g = 0;
+    while (g + 1 < tb.G && row >= tb.row0[g + 1]) ++g;
+    return g;
+}
+
+// job 1: dS[i, c..c+3] = bf16(s_g * sum_chunks part_ds);  job 2: dB[g, n, c..c+3] (+)= sum over tiles of g
+__global__ void __launch_bounds__(256) finalize_ds_db_kernel(FinalizeArgs p, int blocks_ds) {
+    const int r4 = p.r >> 2;
+    if ((int)blockIdx.x < blocks_ds) {
+        const int64_t idx = blockIdx.x * 256ll + threadIdx.x;
+        if (idx >= (int64_t)p.M * r4) return;
+        const int row = (int)(idx / r4);
+        const float s = p.tb.s[segment_of_row(p.tb, row)];
+        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int ch = 0; ch < p.chunks; ++ch) v += *(const f32x4*)(p.part_ds + ((int64_t)ch * p.M * r4 + idx) * 4);
+        u32x2 o;
+        o.x = pack_bf16x2(v[0] * s, v[1] * s);
+        o.y = pack_bf16x2(v[2] * s, v[3] * s);
+        *(u32x2*)(p.dS + idx * 4) = o;
+    } else {
+        const int64_t per_g = (int64_t)p.N * r4;
+        const int64_t idx = (blockIdx.x - blocks_ds) * 256ll + threadIdx.x;
+        if (idx >= per_g * p.tb.G) return;
+        const int g = (int)(idx / per_g);
+        const int64_t e = idx - g * per_g;
+        int tile0 = 0;
+        for (int gg = 0; gg < g; ++gg) tile0 += (p.tb.row0[gg + 1] - p.tb.row0[gg] + kRowTile - 1) / kRowTile;
+        const int nt = (p.tb.row0[g + 1] - p.tb.row0[g] + kRowTile - 1) / kRowTile;
+        if (nt == 0 && p.accumulate) return;
+        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int tl = tile0; tl < tile0 + nt; ++tl) v += *(const f32x4*)(p.part_db + ((int64_t)tl * per_g + e) * 4);
+        f32x4* out = (f32x4*)(p.dB + idx * 4);
+        *out = p.accumulate ? *out + v : v;
+    }
+}
+
+// dA[g, c, j..j+3] (+)= q_g * sum over the row tiles of segment g
+__global__ void __launch_bounds__(256) finalize_da_kernel(FinalizeArgs p) {
+    const int64_t per_g = (int64_t)p.r * (p.K >> 2);
+    const int64_t idx = blockIdx.x * 256ll + threadIdx.x;
+    if (idx >= per_g * p.tb.G) return;
+    const int g = (int)(idx / per_g);
+    const int64_t e = idx - g * per_g;
+    int tile0 = 0;
+    for (int gg = 0; gg < g; ++gg) tile0 += (p.tb.row0[gg + 1] - p.tb.row0[gg] + kRowTile - 1) / kRowTile;
+    const int nt = (p.tb.row0[g + 1] - p.tb.row0[g] + kRowTile - 1) / kRowTile;
+    if (nt == 0 && p.accumulate) return;
+    f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int tl = tile0; tl < tile0 + nt; ++tl) v += *(const f32x4*)(p.part_da + ((int64_t)tl * per_g + e) * 4);
+    v *= p.tb.q[g];
+    f32x4* out = (f32x4*)(p.dA + idx * 4);
+    *out = p.accumulate ? *out + v : v;
+}
+
+hipError_t launch_finalize_ds_db(const FinalizeArgs& a, hipStream_t st) {
+    const int64_t n_ds = (int64_t)a.M * (a.r >> 2), n_db = (int64_t)a.tb.G * a.N * (a.r >> 2);
+    const int blocks_ds = (int)((n_ds + 255) / 256), blocks_db = (int)((n_db + 255) / 256);
+    hipLaunchKernelGGL(finalize_ds_db_kernel, dim3(blocks_ds + blocks_db), dim3(256), 0, st, a, blocks_ds);
+    return hipGetLastError();
+}
+
+hipError_t launch_finalize_da(const FinalizeArgs& a, hipStream_t st) {
+    const int64_t n = (int64_t)a.tb.G * a.r * (a.K >> 2);
+    hipLaunchKernelGGL(finalize_da_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace lf

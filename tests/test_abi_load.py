@@ -1,0 +1,75 @@
+"""The C-ABI library loads and exports every symbol the header declares; host-side validation
+paths return the documented status codes without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "lorafusion.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2510_00206_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return binding.load_library()
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:multi_)?lora_[a-z_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert {"lora_fwd", "lora_bwd", "multi_lora_fwd", "multi_lora_bwd"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_status_strings(lib):
+    assert lib.lora_version() >= 100
+    assert lib.lora_status_string(0) == b"ok"
+    for code in range(1, 9):
+        assert len(lib.lora_status_string(code)) > 3
+
+
+def test_host_side_validation_needs_no_gpu(lib):
+    """Validation fails before anything is enqueued, so these calls are safe on a CPU-only box."""
+    ok_ptr = C.c_void_p(0x1000)
+    f = lib.lora_fwd
+    assert f(None, ok_ptr, ok_ptr, ok_ptr, 64, 64, 64, 16, 1.0, 0.1, 1, ok_ptr, ok_ptr, None) == 1
+    assert f(ok_ptr, ok_ptr, ok_ptr, ok_ptr, -1, 64, 64, 16, 1.0, 0.1, 1, ok_ptr, ok_ptr, None) == 2
+    assert f(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 64, 0, 64, 16, 1.0, 0.1, 1, ok_ptr, ok_ptr, None) == 2
+    assert f(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 64, 96, 64, 16, 1.0, 0.1, 1, ok_ptr, ok_ptr, None) == 7
+    assert f(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 64, 64, 64, 8, 1.0, 0.1, 1, ok_ptr, ok_ptr, None) == 7
+    assert f(C.c_void_p(0x1008), ok_ptr, ok_ptr, ok_ptr, 64, 64, 64, 16, 1.0, 0.1, 1, ok_ptr, ok_ptr, None) == 3
+    for bad_p in (-0.1, 1.0, float("nan")):
+        assert f(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 64, 64, 64, 16, 1.0, bad_p, 1, ok_ptr, ok_ptr, None) == 4
+    assert f(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 64, 64, 64, 16, float("inf"), 0.1, 1, ok_ptr, ok_ptr, None) == 4
+    assert f(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 0, 64, 64, 16, 1.0, 0.1, 1, ok_ptr, ok_ptr, None) == 0   # M == 0: no-op
+    # segments
+    offs = (C.c_int64 * 3)(0, 128, 64)
+    s = (C.c_float * 2)(1.0, 1.0)
+    p = (C.c_float * 2)(0.1, 0.1)
+    sd = (C.c_uint64 * 2)(1, 2)
+    m = lib.multi_lora_fwd
+    assert m(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 64, 64, 64, 16, 2, offs, s, p, sd, ok_ptr, ok_ptr, None) == 5
+    offs = (C.c_int64 * 3)(0, 32, 128)
+    assert m(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 64, 64, 64, 16, 2, offs, s, p, sd, ok_ptr, ok_ptr, None) == 5
+    assert m(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 64, 64, 64, 16, 65, offs, s, p, sd, ok_ptr, ok_ptr, None) == 7
+    # workspace
+    need = lib.lora_bwd_workspace_bytes(256, 128, 128, 16, 1)
+    assert need > 0 and lib.lora_bwd_workspace_bytes(256, 100, 128, 16, 1) == 0
+    ws = C.c_void_p(0x100000)
+    b = lib.lora_bwd
+    assert b(ok_ptr, ok_ptr, ok_ptr, ok_ptr, ok_ptr, ok_ptr, 256, 128, 128, 16, 1.0, 0.1, 1,
+             ok_ptr, ok_ptr, ok_ptr, 0, ws, need - 1, None) == 6
+    assert b(ok_ptr, ok_ptr, ok_ptr, ok_ptr, ok_ptr, ok_ptr, 256, 128, 128, 16, 1.0, 0.1, 1,
+             ok_ptr, ok_ptr, ok_ptr, 0, None, need, None) == 1
+    assert lib.lora_debug_mask(4, 4, 1.5, 1, ok_ptr, None) == 4

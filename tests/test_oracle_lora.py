@@ -204,3 +204,22 @@ def test_expected_value_of_dropped_input():
         acc += oracle.lora_fwd(X, W, A, B, 1.0, 0.25, sd)[1]
     err = np.abs(acc / n - ref).max()
     assert err < 6 * (0.25 / 0.75 / n) ** 0.5 * np.abs(X).max() * np.abs(A).max() * 64 ** 0.5
+
+
+def test_row_sampling_matches_full_evaluation():
+    g = np.random.default_rng(20)
+    M, K, N, r, G = 24, 10, 6, 2, 3
+    offs = [0, 9, 9, 24]
+    X, W = g.standard_normal((M, K)), g.standard_normal((N, K))
+    A, B = g.standard_normal((G, r, K)), g.standard_normal((G, N, r))
+    dY = g.standard_normal((M, N))
+    s, p, seeds = [1.0, 2.0, 0.5], [0.3, 0.2, 0.4], [3, 4, 5]
+    rows = np.array([23, 0, 8, 9, 15])
+    Y, S = oracle.multi_lora_fwd(X, W, A, B, offs, s, p, seeds)
+    Ys, Ss = oracle.multi_lora_fwd(X, W, A, B, offs, s, p, seeds, rows=rows)
+    assert np.array_equal(Ys, Y[rows]) and np.array_equal(Ss, S)
+    full = oracle.multi_lora_bwd(X, W, A, B, dY, offs, s, p, seeds)
+    samp = oracle.multi_lora_bwd(X, W, A, B, dY, offs, s, p, seeds, rows=rows)
+    assert np.array_equal(samp[0], full[0][rows])
+    for a, b in zip(samp[1:], full[1:]):
+        assert np.array_equal(a, b)
