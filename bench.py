@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused LoRA linear layer, forward + backward, on one MI355X.
+
+One "step" is one pass of the whole hot path - lora_fwd (operations 1-2) then lora_bwd
+(operations 3-5, dX, dA and dB) - over one batch of synthetic bf16 inputs that are already
+resident in HBM.  The default workload is the 8B-style attention projection (M=8192 tokens,
+K=N=4096, r=16, s=2, p=0.1), the configuration the headline metric is quoted on.
+
+Prints ONE JSON line: whole-job TFLOP/s on the algorithmic FLOP count 4MKN + 6Mr(K+N), tokens/s,
+the roofline record of the dominant kernel (timed live with HIP events on the launch stream) and
+the CPU oracle timed on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def read_traffic(workload: str):
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
+    (profiles/hbm_traffic_<workload>.txt, line 'dominant_kernel_bytes_per_launch: N'); None if absent."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    try:
+        with open(path) as f:
+            for ln in f:
+                if ln.startswith("dominant_kernel_bytes_per_launch:"):
+                    return float(ln.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c2", help="c1..c5 (default c2, the headline configuration)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a 1 GiB device copy 10 times (reference reading for HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2510_00206_amd import binding, workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    binding.load_library()                     # fails loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "launches": 10}))
+        return
+    layers = workloads.CONFIGS[args.workload]
+
+    # inputs, outputs and workspaces resident in HBM before the timed region
+    state = []
+    for li, L in enumerate(layers):
+        X, W, A, B, dY = (t.to(dev) for t in workloads.make_inputs(L, layer_index=li))
+        st = dict(L=L, X=X, W=W, A=A, B=B, dY=dY,
+                  Y=torch.empty((L.M, L.N), dtype=torch.bfloat16, device=dev),
+                  S=torch.empty((L.M, L.r), dtype=torch.bfloat16, device=dev),
+                  dA=torch.empty((L.G, L.r, L.K), dtype=torch.float32, device=dev),
+                  dB=torch.empty((L.G, L.N, L.r), dtype=torch.float32, device=dev),
+                  ws=binding.alloc_workspace(L.M, L.K, L.N, L.r, L.G, dev),
+                  s=[L.s] * L.G, p=[L.p] * L.G)
+        state.append(st)
+
+    def step():
+        for st in state:
+            L = st["L"]
+            binding.multi_lora_fwd(st["X"], st["W"], st["A"], st["B"], L.seg_offsets, st["s"], st["p"], L.seeds,
+                                   Y=st["Y"], S=st["S"])
+            st["dX"] = binding.multi_lora_bwd(st["X"], st["W"], st["A"], st["B"], st["S"], st["dY"], L.seg_offsets,
+                                              st["s"], st["p"], L.seeds, dA=st["dA"], dB=st["dB"],
+                                              workspace=st["ws"], dX=st.get("dX"))[0]
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    flops = sum(st["L"].flops for st in state)
+    tokens = state[0]["L"].M                    # the layers of one configuration share the token batch
+    fused_bytes = sum(st["L"].fused_bytes for st in state)
+    tflops = flops / (ms_per_step * 1e-3) / 1e12
+
+    # per-kernel durations: same steps again with HIP events around every launch (on the launch stream)
+    binding.profile_begin()
+    for _ in range(args.steps):
+        step()
+    prof = binding.profile_end()
+    kernels_us = {k: (ms / n * 1e3 if n else 0.0) for k, (ms, n) in prof.items()}
+    launches = {k: n for k, (ms, n) in prof.items()}
+    # dominant kernel: the dX GEMM (operation 5); its algorithmic FLOPs per launch = 2MNK + 2MrK,
+    # averaged over the launches of one step (one per layer)
+    dom = "dx_gemm" if kernels_us["dx_gemm"] >= kernels_us["fwd_gemm"] else "fwd_gemm"
+    if dom == "dx_gemm":
+        dom_flops = sum(2 * st["L"].M * st["L"].N * st["L"].K + 2 * st["L"].M * st["L"].r * st["L"].K for st in state)
+    else:
+        dom_flops = sum(2 * st["L"].M * st["L"].N * st["L"].K + 2 * st["L"].M * st["L"].r * st["L"].N for st in state)
+    dom_flops /= len(state)
+    achieved = dom_flops / (kernels_us[dom] * 1e-6) / 1e12
+    traffic = read_traffic(args.workload)
+
+    out = {
+        "metric": "fused LoRA linear fwd+bwd TFLOP/s and tokens/s at 1 MI355X; HBM bytes/token",
+        "value": round(tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": args.workload + ": " + ", ".join(
+            f"{st['L'].name} M={st['L'].M} K={st['L'].K} N={st['L'].N} r={st['L'].r} G={st['L'].G} p={st['L'].p}"
+            for st in state)},
+        "tokens_per_s": round(tokens / (ms_per_step * 1e-3), 1),
+        "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "algorithmic_hbm_bytes_per_token": round(fused_bytes / tokens, 1),
+        "kernel_us": {k: round(v, 2) for k, v in kernels_us.items()},
+        "kernel_launches": launches,
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic},
+    }
+
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        L0 = state[0]["L"]
+        f64 = lambda t: t.to(torch.float64).cpu().numpy()
+        Xd, Wd, Ad, Bd, dYd = (f64(state[0][k]) for k in ("X", "W", "A", "B", "dY"))
+        s, p = [L0.s] * L0.G, [L0.p] * L0.G
+        t0 = time.perf_counter()
+        oracle.multi_lora_fwd(Xd, Wd, Ad, Bd, L0.seg_offsets, s, p, L0.seeds)
+        oracle.multi_lora_bwd(Xd, Wd, Ad, Bd, dYd, L0.seg_offsets, s, p, L0.seeds)
+        cpu_s = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        out["cpu_baseline"] = {"value": round(L0.flops / cpu_s / 1e12, 4), "unit": "TFLOP/s", "cores": int(cores),
+                               "kind": "oracle", "sample": f"one full fwd+bwd of layer {L0.name} "
+                               f"(M={L0.M}), fp64 numpy, {cpu_s:.1f} s"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

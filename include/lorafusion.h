@@ -108,6 +108,25 @@ lora_status multi_lora_bwd(const lora_bf16* X, const lora_bf16* W, const lora_bf
 lora_status lora_debug_mask(int64_t M, int64_t K, float p, uint64_t seed, uint8_t* keep,
                             lora_stream stream);
 
+/* Diagnostic per-kernel timing for benchmarks.  Between lora_profile_begin() and
+ * lora_profile_end() every kernel the entry points above enqueue is bracketed by a pair of HIP
+ * events on the caller's stream (the events are created by the library: do not use inside graph
+ * capture).  lora_profile_end() waits for the recorded events, adds the elapsed milliseconds and
+ * the launch count of each kernel into ms_total / launches (host arrays of LORA_PROF_KERNELS
+ * entries, indexed by lora_prof_kernel) and switches timing off.  Not thread safe. */
+typedef enum {
+    LORA_PROF_DOWN = 0,       /* operation (1): dropout + down-projection            */
+    LORA_PROF_FWD_GEMM = 1,   /* operation (2): Y = X W + S' B                        */
+    LORA_PROF_DS_DB = 2,      /* operation (3): dS and dB partials from one dY pass   */
+    LORA_PROF_FIN_DS_DB = 3,  /* fixed-order reduction of the dS / dB partials        */
+    LORA_PROF_DA = 4,         /* operation (4): dA partials from one X pass           */
+    LORA_PROF_FIN_DA = 5,     /* fixed-order reduction of the dA partials             */
+    LORA_PROF_DX_GEMM = 6,    /* operation (5): dX = dY W^T + mask*q*(dS A^T)         */
+    LORA_PROF_KERNELS = 7
+} lora_prof_kernel;
+lora_status lora_profile_begin(void);
+lora_status lora_profile_end(float* ms_total, int32_t* launches);
+
 const char* lora_status_string(lora_status st);
 int lora_version(void);
 

@@ -50,7 +50,9 @@ def load_library() -> C.CDLL:
         lib.lora_unfused_workspace_bytes.restype = SZ
         lib.lora_unfused_fwd.argtypes = [P, P, P, P, I64, I64, I64, I32, F, F, U64, P, P, SZ, P]
         lib.lora_unfused_bwd.argtypes = [P, P, P, P, P, I64, I64, I64, I32, F, F, U64, P, P, P, P, SZ, P]
-    for f in ("lora_fwd", "lora_bwd", "multi_lora_fwd", "multi_lora_bwd", "lora_debug_mask"):
+    lib.lora_profile_end.argtypes = [C.POINTER(F), C.POINTER(I32)]
+    for f in ("lora_fwd", "lora_bwd", "multi_lora_fwd", "multi_lora_bwd", "lora_debug_mask",
+              "lora_profile_begin", "lora_profile_end"):
         getattr(lib, f).restype = C.c_int
     _lib = lib
     return lib
@@ -101,11 +103,14 @@ def lora_fwd(X, W, A, B, s, p, seed, Y=None, S=None):
     return Y, S
 
 
-def lora_bwd(X, W, A, B, S, dY, s, p, seed, need_dx=True, dA=None, dB=None, accumulate=False, workspace=None):
+def lora_bwd(X, W, A, B, S, dY, s, p, seed, need_dx=True, dA=None, dB=None, accumulate=False, workspace=None,
+             dX=None):
     """dX [M,K] bf16 (or None), dA [r,K] fp32, dB [N,r] fp32."""
     M, K = X.shape
     N, r = B.shape
-    dX = torch.empty((M, K), dtype=torch.bfloat16, device=X.device) if need_dx else None
+    if need_dx and dX is None:
+        dX = torch.empty((M, K), dtype=torch.bfloat16, device=X.device)
+    dX = dX if need_dx else None
     dA = torch.empty((r, K), dtype=torch.float32, device=X.device) if dA is None else dA
     dB = torch.empty((N, r), dtype=torch.float32, device=X.device) if dB is None else dB
     ws = alloc_workspace(M, K, N, r, 1, X.device) if workspace is None else workspace
@@ -128,11 +133,13 @@ def multi_lora_fwd(X, W, A, B, seg_offsets: Sequence[int], s, p, seeds, Y=None, 
 
 
 def multi_lora_bwd(X, W, A, B, S, dY, seg_offsets, s, p, seeds, need_dx=True, dA=None, dB=None,
-                   accumulate=False, workspace=None):
+                   accumulate=False, workspace=None, dX=None):
     """dX [M,K] bf16 (or None), dA [G,r,K] fp32, dB [G,N,r] fp32."""
     M, K = X.shape
     G, N, r = B.shape
-    dX = torch.empty((M, K), dtype=torch.bfloat16, device=X.device) if need_dx else None
+    if need_dx and dX is None:
+        dX = torch.empty((M, K), dtype=torch.bfloat16, device=X.device)
+    dX = dX if need_dx else None
     dA = torch.empty((G, r, K), dtype=torch.float32, device=X.device) if dA is None else dA
     dB = torch.empty((G, N, r), dtype=torch.float32, device=X.device) if dB is None else dB
     ws = alloc_workspace(M, K, N, r, G, X.device) if workspace is None else workspace
@@ -148,3 +155,18 @@ def lora_debug_mask(M, K, p, seed, device="cuda"):
     keep = torch.empty((M, K), dtype=torch.uint8, device=device)
     _check(load_library().lora_debug_mask(M, K, p, seed, _ptr(keep), _stream()))
     return keep
+
+
+PROF_KERNELS = ("down", "fwd_gemm", "ds_db", "finalize_ds_db", "da", "finalize_da", "dx_gemm")
+
+
+def profile_begin():
+    _check(load_library().lora_profile_begin())
+
+
+def profile_end():
+    """{kernel name: (total ms, launches)} of the kernels enqueued since profile_begin()."""
+    n = len(PROF_KERNELS)
+    ms, cnt = (C.c_float * n)(), (C.c_int32 * n)()
+    _check(load_library().lora_profile_end(ms, cnt))
+    return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(PROF_KERNELS)}

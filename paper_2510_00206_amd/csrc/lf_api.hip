@@ -4,6 +4,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <vector>
+
 #include "../../include/lorafusion.h"
 #include "lf_internal.h"
 
@@ -50,6 +52,23 @@ lora_status build_table(AdapterTable& tb, int64_t M, int32_t G, const int64_t* o
     return LORA_OK;
 }
 
+// Optional per-kernel timing (diagnostic): HIP events bracket every launch on the caller's stream.
+struct ProfRec { hipEvent_t beg, end; int id; };
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+
+template <typename F>
+hipError_t timed(int id, hipStream_t st, F&& launch) {
+    if (!g_prof_on) return launch();
+    ProfRec r{nullptr, nullptr, id};
+    if (hipEventCreate(&r.beg) != hipSuccess || hipEventCreate(&r.end) != hipSuccess) return hipErrorUnknown;
+    hipEventRecord(r.beg, st);
+    hipError_t e = launch();
+    hipEventRecord(r.end, st);
+    g_prof.push_back(r);
+    return e;
+}
+
 struct Workspace {
     lora_bf16* dS; float* part_ds; float* part_db; float* part_da; size_t bytes;
 };
@@ -72,9 +91,9 @@ lora_status fwd_impl(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A,
                      int64_t M, int64_t K, int64_t N, int32_t r, const AdapterTable& tb,
                      lora_bf16* Y, lora_bf16* S, hipStream_t st) {
     DownArgs d{X, A, S, (int)M, (int)K, r, tb};
-    if (launch_down(d, st) != hipSuccess) return LORA_ERR_HIP;
+    if (timed(LORA_PROF_DOWN, st, [&] { return launch_down(d, st); }) != hipSuccess) return LORA_ERR_HIP;
     FwdGemmArgs f{X, W, S, B, Y, (int)M, (int)K, (int)N, r, 0, 0, tb};
-    if (launch_fwd_gemm(f, st) != hipSuccess) return LORA_ERR_HIP;
+    if (timed(LORA_PROF_FWD_GEMM, st, [&] { return launch_fwd_gemm(f, st); }) != hipSuccess) return LORA_ERR_HIP;
     return LORA_OK;
 }
 
@@ -85,16 +104,16 @@ lora_status bwd_impl(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A,
     const Workspace ws = carve(workspace, M, K, N, r, tb.G);
     const int chunks = (int)((N + kStreamChunk - 1) / kStreamChunk);
     StreamArgs s3{dY, S, B, ws.part_db, ws.part_ds, (int)M, (int)N, r, 0, 0, tb};
-    if (launch_stream_dsdb(s3, st) != hipSuccess) return LORA_ERR_HIP;
+    if (timed(LORA_PROF_DS_DB, st, [&] { return launch_stream_dsdb(s3, st); }) != hipSuccess) return LORA_ERR_HIP;
     FinalizeArgs fin{ws.part_ds, ws.dS, ws.part_db, dB, ws.part_da, dA,
                      (int)M, (int)K, (int)N, r, chunks, accumulate, tb};
-    if (launch_finalize_ds_db(fin, st) != hipSuccess) return LORA_ERR_HIP;
+    if (timed(LORA_PROF_FIN_DS_DB, st, [&] { return launch_finalize_ds_db(fin, st); }) != hipSuccess) return LORA_ERR_HIP;
     StreamArgs s4{X, ws.dS, nullptr, ws.part_da, nullptr, (int)M, (int)K, r, 0, 0, tb};
-    if (launch_stream_da(s4, st) != hipSuccess) return LORA_ERR_HIP;
-    if (launch_finalize_da(fin, st) != hipSuccess) return LORA_ERR_HIP;
+    if (timed(LORA_PROF_DA, st, [&] { return launch_stream_da(s4, st); }) != hipSuccess) return LORA_ERR_HIP;
+    if (timed(LORA_PROF_FIN_DA, st, [&] { return launch_finalize_da(fin, st); }) != hipSuccess) return LORA_ERR_HIP;
     if (dX) {
         DxGemmArgs g5{dY, W, ws.dS, A, dX, (int)M, (int)K, (int)N, r, 0, 0, tb};
-        if (launch_bwd_dx(g5, st) != hipSuccess) return LORA_ERR_HIP;
+        if (timed(LORA_PROF_DX_GEMM, st, [&] { return launch_bwd_dx(g5, st); }) != hipSuccess) return LORA_ERR_HIP;
     }
     return LORA_OK;
 }
@@ -190,5 +209,29 @@ const char* lora_status_string(lora_status st) {
 }
 
 int lora_version(void) { return 100; }
+
+lora_status lora_profile_begin(void) {
+    for (ProfRec& r : g_prof) { hipEventDestroy(r.beg); hipEventDestroy(r.end); }
+    g_prof.clear();
+    g_prof_on = true;
+    return LORA_OK;
+}
+
+lora_status lora_profile_end(float* ms_total, int32_t* launches) {
+    g_prof_on = false;
+    if (!ms_total || !launches) return LORA_ERR_NULL;
+    for (int i = 0; i < LORA_PROF_KERNELS; ++i) { ms_total[i] = 0.f; launches[i] = 0; }
+    lora_status st = LORA_OK;
+    for (ProfRec& r : g_prof) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.end) != hipSuccess || hipEventElapsedTime(&ms, r.beg, r.end) != hipSuccess)
+            st = LORA_ERR_HIP;
+        else if (r.id >= 0 && r.id < LORA_PROF_KERNELS) { ms_total[r.id] += ms; launches[r.id] += 1; }
+        hipEventDestroy(r.beg);
+        hipEventDestroy(r.end);
+    }
+    g_prof.clear();
+    return st;
+}
 
 }  // extern "C"
