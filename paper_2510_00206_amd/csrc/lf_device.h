@@ -76,6 +76,12 @@ __device__ __forceinline__ uint32_t hash_word(RowKey rk, uint32_t cp) {
     return x;
 }
 
+// Same word from x = rk.a + cp * kGold already formed (consecutive pairs differ by kGold).
+__device__ __forceinline__ uint32_t hash_word_at(RowKey rk, uint32_t x) {
+    x ^= x >> 16; x *= kM1; x += rk.b; x ^= x >> 15; x *= kM2; x ^= x >> 16;
+    return x;
+}
+
 // AND-mask for a packed pair of bf16 (even column in the low half).
 __device__ __forceinline__ uint32_t keep_pair_mask(uint32_t w, uint32_t T) {
     return ((w & 0xFFFFu) >= T ? 0x0000FFFFu : 0u) | ((w >> 16) >= T ? 0xFFFF0000u : 0u);

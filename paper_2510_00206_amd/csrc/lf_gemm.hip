@@ -3,10 +3,11 @@
 //   operation (5)  dX = dY W^T + mask*q*(dS A^T)   (base gradient GEMM + masked LoRA gradient)
 // with storage layouts X [M,K], W [N,K], S' [M,r], B [N,r], dY [M,N], dS [M,r], A [r,K].
 //
-// Both run a 256x256 output tile per workgroup (8 waves, each 128x64 of the tile as 4x2 MFMA
-// 32x32x16 bf16 blocks, fp32 accumulators), stage 64-deep operand slabs through swizzled LDS,
-// double-buffered, and treat the rank-r LoRA term as extra contraction steps on the same
-// accumulators.  (2) contracts over the contiguous dimension of both operands; (5) contracts over
+// Both run a 256x256 output tile per workgroup: 4 waves, one per SIMD, each owning 128x128 of the
+// tile as 4x4 MFMA 32x32x16 bf16 blocks (256 fp32 accumulator registers; sixteen independent
+// accumulator chains per wave is what keeps the matrix pipe full on this chip).  64-deep operand
+// slabs are copied global -> LDS without passing through registers, double-buffered, and the
+// rank-r LoRA term rides as extra contraction steps on the same accumulators.  (2) contracts over the contiguous dimension of both operands; (5) contracts over
 // the row dimension of W (and of A), which it reads from LDS with transposing loads so that no
 // transposed copy of the frozen weight is ever kept.
 #include "lf_device.h"
@@ -15,7 +16,8 @@
 namespace lf {
 
 constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int NTHREADS = 512;
+constexpr int NTHREADS = 256;
+constexpr int NWAVES = NTHREADS / 64;
 constexpr int TILE_BYTES = BM * BK * 2;            // one 256x64 (or 64x256) bf16 slab: 32 KB
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;        // both operands
 constexpr int GEMM_LDS_BYTES = 2 * STAGE_BYTES;    // double buffered: 128 KB
@@ -38,130 +40,260 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
 }
 
 // ---- slab movement ------------------------------------------------------------------------------
-// Row-operand slab: 256 rows x 64 contraction elements, each row 8 chunks of 16 B.
-// Thread t moves chunk (t & 7) of rows (t >> 3) + 64*i, i = 0..3.
-struct RowSlabRegs { u32x4 v[4]; };
+// Slabs go from global memory straight into LDS (16 bytes per lane, no register staging): one wave
+// instruction fills 1024 contiguous LDS bytes, lane l writing bytes [16 l, 16 l + 16), so the
+// swizzle is applied by choosing which global chunk each lane fetches.  The load is issued from
+// inline assembly: the LDS destination (M0) and the completion wait are managed by hand, so that
+// the copy of the next slab stays in flight while the current one is consumed.
+constexpr int PASSES = 2048 / NTHREADS;              // 16-byte chunks per thread per 32 KB slab: 8
 
-__device__ __forceinline__ void load_row_slab(RowSlabRegs& r, const lora_bf16* base, int64_t ld,
-                                              int rows_valid, int k0, int nchunk_valid) {
-    const int t = threadIdx.x;
-    const int chunk = t & 7;
-    const int ch = min(chunk, nchunk_valid - 1);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = min((t >> 3) + 64 * i, rows_valid - 1);
-        r.v[i] = *(const u32x4*)(base + (int64_t)row * ld + k0 + ch * 8);
-    }
+__device__ __forceinline__ uint32_t lds_addr_of(const char* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
 }
 
-__device__ __forceinline__ void store_row_slab(const RowSlabRegs& r, char* lds) {
-    const int t = threadIdx.x;
-    const int chunk = t & 7;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = (t >> 3) + 64 * i;
-        *(u32x4*)(lds + tile_off(row, chunk, 8)) = r.v[i];
-    }
+__device__ __forceinline__ void copy16_to_lds(const char* uniform_base, uint32_t lane_byte_off, uint32_t lds_wave_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_wave_addr), "v"(lane_byte_off), "s"(uniform_base) : "memory");
 }
 
-// Column-operand slab for (5): 64 contraction rows x 256 output columns, each row 32 chunks.
-// Thread t moves chunk (t & 31) of rows (t >> 5) + 16*i, i = 0..3.
-__device__ __forceinline__ void load_col_slab(RowSlabRegs& r, const lora_bf16* base, int64_t ld,
-                                              int rows_valid, int c0, int cols_valid) {
-    const int t = threadIdx.x;
-    const int chunk = min(t & 31, (cols_valid >> 3) - 1);
+__device__ __forceinline__ void wait_slab_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Per-lane source offsets of one slab (bytes from the slab's first element), one per pass.
+struct SlabLanes { uint32_t off[PASSES]; };
+
+// Row-operand slab: 256 rows x 64 contraction elements, each row 8 chunks of 16 B (128 B).
+// Wave w, pass i fills rows 8*(NWAVES*i + w) .. +7; lane l is (row l >> 3, physical chunk l & 7).
+__device__ __forceinline__ SlabLanes row_slab_lanes(int64_t ld, int rows_valid, int nchunk_valid) {
+    const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
+    SlabLanes s;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = min((t >> 5) + 16 * i, rows_valid - 1);
-        r.v[i] = *(const u32x4*)(base + (int64_t)row * ld + c0 + chunk * 8);
+    for (int i = 0; i < PASSES; ++i) {
+        const int row = 8 * (NWAVES * i + w) + (l >> 3);
+        const int chunk = min((l & 7) ^ swz(row), nchunk_valid - 1);
+        s.off[i] = (uint32_t)((min(row, rows_valid - 1) * ld + chunk * 8) * 2);
     }
+    return s;
 }
 
-__device__ __forceinline__ void store_col_slab(const RowSlabRegs& r, char* lds) {
-    const int t = threadIdx.x;
-    const int chunk = t & 31;
+// Column-operand slab for (5): 64 contraction rows x 256 output columns, each row 32 chunks (512 B).
+// Wave w, pass i fills rows 2*(NWAVES*i + w), +1; lane l is (row l >> 5, physical chunk l & 31).
+__device__ __forceinline__ SlabLanes col_slab_lanes(int64_t ld, int rows_valid, int cols_valid) {
+    const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
+    SlabLanes s;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = (t >> 5) + 16 * i;
-        *(u32x4*)(lds + tile_off(row, chunk, 32)) = r.v[i];
+    for (int i = 0; i < PASSES; ++i) {
+        const int row = 2 * (NWAVES * i + w) + (l >> 5);
+        const int chunk = min((l & 31) ^ swz(row), (cols_valid >> 3) - 1);
+        s.off[i] = (uint32_t)((min(row, rows_valid - 1) * ld + chunk * 8) * 2);
     }
+    return s;
+}
+
+// Enqueue one slab: `src` is the (workgroup-uniform) address of the slab's first element.
+__device__ __forceinline__ void load_slab(uint32_t lds_slab_addr, const lora_bf16* src, const SlabLanes& s) {
+    const uint32_t wave = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i)
+        copy16_to_lds((const char*)src, s.off[i], lds_slab_addr + i * (NWAVES * 1024) + wave);
 }
 
 // ---- fragment reads -----------------------------------------------------------------------------
-// 32 tile rows x 16 contraction elements from a row-operand slab: lane l holds row (l & 31),
-// contraction elements 8*(l >> 5) .. +7 of sub-step kk.
-__device__ __forceinline__ bf16x8 read_row_frag(const char* lds, int row0, int kk) {
-    const int l = threadIdx.x & 63;
-    const u32x4 v = *(const u32x4*)(lds + tile_off(row0 + (l & 31), 2 * kk + (l >> 5), 8));
-    return __builtin_bit_cast(bf16x8, v);
-}
-
-// Same fragment (32 output columns x 16 contraction rows) from a column-operand slab, through two
-// transposing reads: lane l holds column (l & 31), contraction rows 16*kk + 8*(l >> 5) .. +7.
-__device__ __forceinline__ bf16x8 read_col_frag(const char* lds, int col0, int kk) {
-    const int l = threadIdx.x & 63;
-    const int i16 = l & 15;
-    const int c0 = col0 + ((l >> 4) & 1) * 16;
-    const int r0 = 16 * kk + 8 * (l >> 5);
-    const s16x4 lo = lds_read_tr(lds, tr_off(r0, c0, i16, 32));
-    const s16x4 hi = lds_read_tr(lds, tr_off(r0 + 4, c0, i16, 32));
-    return join_tr(lo, hi);
-}
-
 #define LF_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
 
-// One slab of contraction (nkk sub-steps of 16) on the wave's 128x64 part of the tile.
-// `out` operand: the one whose rows become the 4 consecutive output elements a lane owns
-// (W in (2), W^T / A^T in (5)); `tok` operand: the token-row operand (X, S', dY, dS).
+// Per-lane LDS offsets of the MFMA operand fragments.
+//  row slab: 32 tile rows x 16 contraction elements, lane l holds row (l & 31), elements
+//            8*(l >> 5) .. +7 of sub-step kk  -> row_off[kk] (+ 4096 bytes per 32 tile rows)
+//  col slab: 32 output columns x 16 contraction rows through two transposing reads, lane l holds
+//            column (l & 31), rows 16*kk + 8*(l >> 5) + {0..3 | 4..7} -> col_off[ni & 1][half]
+//            (+ 8192 bytes per sub-step kk, + 128 bytes per 64 columns)
+struct FragLanes { int row_off[4]; int col_off[2][2]; };
+
+__device__ __forceinline__ FragLanes frag_lanes() {
+    const int l = threadIdx.x & 63;
+    FragLanes f;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) f.row_off[kk] = tile_off(l & 31, 2 * kk + (l >> 5), 8);
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            f.col_off[ni][h] = tr_off(8 * (l >> 5) + 4 * h, ni * 32 + ((l >> 4) & 1) * 16, l & 15, 32);
+    return f;
+}
+
+struct Frags { bf16x8 fo[4], ft[4]; };
+
+// lds_tok / lds_out already include the wave's row (wm*128 rows) and column (wn*128) origin.
+// row_off_kk: fl.row_off[kk]; col_step: kk * 8192.
 template <bool OUT_IS_COL_SLAB>
-__device__ __forceinline__ void mma_slab(f32x16 (&acc)[4][2], const char* lds_tok, const char* lds_out,
-                                         int wm, int wn, int nkk) {
+__device__ __forceinline__ void read_frags(Frags& f, const char* lds_tok, const char* lds_out,
+                                           const FragLanes& fl, int row_off_kk, int col_step) {
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) {
+        if (OUT_IS_COL_SLAB) {
+            const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni & 1][0] + col_step + (ni >> 1) * 128);
+            const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni & 1][1] + col_step + (ni >> 1) * 128);
+            f.fo[ni] = join_tr(lo, hi);
+        } else {
+            f.fo[ni] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_out + row_off_kk + ni * 4096));
+        }
+    }
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+        f.ft[mi] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_tok + row_off_kk + mi * 4096));
+}
+
+// MFMAs of token-row blocks [MI0, MI1) against all four output-column blocks.
+template <int MI0, int MI1>
+__device__ __forceinline__ void mma_frags(f32x16 (&acc)[4][4], const Frags& f) {
+#pragma unroll
+    for (int mi = MI0; mi < MI1; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = LF_MFMA(f.fo[ni], f.ft[mi], acc[mi][ni]);
+}
+
+// What the next slab pair is copied from: two operand slabs of PASSES wave-passes each.
+struct NextSlabs {
+    const char* src_tok; const char* src_out;     // workgroup-uniform addresses of the slabs' first elements
+    SlabLanes lanes_tok, lanes_out;
+    uint32_t lds_tok, lds_out;                    // LDS addresses of the destination slabs (+ this wave's 1024 B)
+    bool valid;
+};
+
+// Copy number J (0 .. 2*PASSES-1) of the next slab pair.
+template <int J>
+__device__ __forceinline__ void issue_copy(const NextSlabs& nx) {
+    if (!nx.valid) return;
+    if (J < PASSES) copy16_to_lds(nx.src_tok, nx.lanes_tok.off[J], nx.lds_tok + J * (NWAVES * 1024));
+    else copy16_to_lds(nx.src_out, nx.lanes_out.off[J - PASSES], nx.lds_out + (J - PASSES) * (NWAVES * 1024));
+}
+
+template <bool OUT_IS_COL_SLAB>
+__device__ __forceinline__ void read_frag_pair(Frags& f, int i, const char* lds_tok, const char* lds_out,
+                                               const FragLanes& fl, int row_off_kk, int col_step) {
+    if (OUT_IS_COL_SLAB) {
+        const s16x4 lo = lds_read_tr(lds_out, fl.col_off[i & 1][0] + col_step + (i >> 1) * 128);
+        const s16x4 hi = lds_read_tr(lds_out, fl.col_off[i & 1][1] + col_step + (i >> 1) * 128);
+        f.fo[i] = join_tr(lo, hi);
+    } else {
+        f.fo[i] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_out + row_off_kk + i * 4096));
+    }
+    f.ft[i] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_tok + row_off_kk + i * 4096));
+}
+
+// One sub-step of 16 MFMAs in four groups of four; before each group the wave issues a quarter of
+// the next sub-step's fragment reads and COPIES global->LDS copies of the next slab pair, so that
+// LDS reads, copy issue and MFMAs are spread evenly instead of queueing behind one another.
+template <bool OUT_IS_COL_SLAB, int KK_NEXT, int COPY0, int COPIES>
+__device__ __forceinline__ void phase(f32x16 (&acc)[4][4], const Frags& cur, Frags& nxt, const char* lds_tok,
+                                      const char* lds_out, const FragLanes& fl, const NextSlabs& nx) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        read_frag_pair<OUT_IS_COL_SLAB>(nxt, g, lds_tok, lds_out, fl, fl.row_off[KK_NEXT], KK_NEXT * 8192);
+        if (COPIES >= 1) {
+            if (g == 0) issue_copy<COPY0 + 0 * COPIES>(nx);
+            if (g == 1) issue_copy<COPY0 + 1 * COPIES>(nx);
+            if (g == 2) issue_copy<COPY0 + 2 * COPIES>(nx);
+            if (g == 3) issue_copy<COPY0 + 3 * COPIES>(nx);
+        }
+        if (COPIES >= 2) {
+            if (g == 0) issue_copy<COPY0 + 0 * COPIES + 1>(nx);
+            if (g == 1) issue_copy<COPY0 + 1 * COPIES + 1>(nx);
+            if (g == 2) issue_copy<COPY0 + 2 * COPIES + 1>(nx);
+            if (g == 3) issue_copy<COPY0 + 3 * COPIES + 1>(nx);
+        }
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) acc[g][ni] = LF_MFMA(cur.fo[ni], cur.ft[g], acc[g][ni]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// One 64-deep slab pair: sub-steps 0..3, the copies of the next slab pair spread over sub-steps 0..2,
+// and in the middle of sub-step 3 the hand-over (copies landed, workgroup barrier) followed by the
+// first fragment reads of the next slab.  On entry f0 holds the fragments of sub-step 0 of the
+// current slab; on exit it holds those of the next slab.
+template <bool OUT_IS_COL_SLAB>
+__device__ __forceinline__ void slab_step(f32x16 (&acc)[4][4], Frags& f0, Frags& f1, const char* cur_tok,
+                                          const char* cur_out, const char* nxt_tok, const char* nxt_out,
+                                          const FragLanes& fl, const NextSlabs& nx) {
+    static_assert(PASSES == 8, "copy schedule below assumes 16 copies per slab pair");
+    __builtin_amdgcn_sched_barrier(0);
+    phase<OUT_IS_COL_SLAB, 1, 0, 2>(acc, f0, f1, cur_tok, cur_out, fl, nx);     // copies 0..7
+    phase<OUT_IS_COL_SLAB, 2, 8, 1>(acc, f1, f0, cur_tok, cur_out, fl, nx);     // copies 8..11
+    phase<OUT_IS_COL_SLAB, 3, 12, 1>(acc, f0, f1, cur_tok, cur_out, fl, nx);    // copies 12..15
+    // sub-step 3
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) acc[g][ni] = LF_MFMA(f1.fo[ni], f1.ft[g], acc[g][ni]);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_slab_loads();
+    __syncthreads();
+#pragma unroll
+    for (int g = 2; g < 4; ++g) {
+        if (nx.valid) {
+            read_frag_pair<OUT_IS_COL_SLAB>(f0, 2 * (g - 2), nxt_tok, nxt_out, fl, fl.row_off[0], 0);
+            read_frag_pair<OUT_IS_COL_SLAB>(f0, 2 * (g - 2) + 1, nxt_tok, nxt_out, fl, fl.row_off[0], 0);
+        }
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) acc[g][ni] = LF_MFMA(f1.fo[ni], f1.ft[g], acc[g][ni]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// A slab with a run-time number of sub-steps (the rank-r LoRA slab: r/16 sub-steps), as one rolled
+// loop so that the accumulators stay in place.
+template <bool OUT_IS_COL_SLAB>
+__device__ __forceinline__ void mma_slab_rolled(f32x16 (&acc)[4][4], const char* lds_tok, const char* lds_out,
+                                                const FragLanes& fl, int nkk) {
+    const int l = threadIdx.x & 63;
+#pragma unroll 1
     for (int kk = 0; kk < nkk; ++kk) {
-        bf16x8 fo[2], ft[4];
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-            fo[ni] = OUT_IS_COL_SLAB ? read_col_frag(lds_out, wn * 64 + ni * 32, kk)
-                                     : read_row_frag(lds_out, wn * 64 + ni * 32, kk);
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi) ft[mi] = read_row_frag(lds_tok, wm * 128 + mi * 32, kk);
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = LF_MFMA(fo[ni], ft[mi], acc[mi][ni]);
+        Frags f;
+        read_frags<OUT_IS_COL_SLAB>(f, lds_tok, lds_out, fl, tile_off(l & 31, 2 * kk + (l >> 5), 8), kk * 8192);
+        mma_frags<0, 4>(acc, f);
     }
 }
 
 // Accumulator element (mi, ni, i) of lane l is output row  wm*128 + mi*32 + (l & 31)  and output
-// column  wn*64 + ni*32 + 8*(i >> 2) + 4*(l >> 5) + (i & 3)  of the tile: a lane owns groups of four
+// column  wn*128 + ni*32 + 8*(i >> 2) + 4*(l >> 5) + (i & 3)  of the tile: a lane owns groups of four
 // consecutive columns of one row.
-template <typename F>
-__device__ __forceinline__ void for_each_quad(int wm, int wn, F&& f) {
+__device__ __forceinline__ void store_tile(const f32x16 (&acc)[4][4], lora_bf16* out, int64_t ld,
+                                           int row_start, int rows_valid, int col_start, int cols_valid,
+                                           int wm, int wn) {
     const int l = threadIdx.x & 63;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+        const int row = wm * 128 + mi * 32 + (l & 31);
+        if (row >= rows_valid) continue;
+        lora_bf16* orow = out + (int64_t)(row_start + row) * ld + col_start;
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int col = wn * 128 + ni * 32 + 8 * g4 + 4 * (l >> 5);
+                if (col < cols_valid) {
+                    const f32x16& a = acc[mi][ni];
+                    u32x2 v;
+                    v.x = pack_bf16x2(a[4 * g4 + 0], a[4 * g4 + 1]);
+                    v.y = pack_bf16x2(a[4 * g4 + 2], a[4 * g4 + 3]);
+                    *(u32x2*)(orow + col) = v;
+                }
+            }
+    }
+}
+
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[4][4]) {
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+        for (int ni = 0; ni < 4; ++ni)
 #pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4)
-                f(mi, ni, g4, wm * 128 + mi * 32 + (l & 31), wn * 64 + ni * 32 + 8 * g4 + 4 * (l >> 5));
-}
-
-__device__ __forceinline__ void store_tile(const f32x16 (&acc)[4][2], lora_bf16* out, int64_t ld,
-                                           int row_start, int rows_valid, int col_start, int cols_valid,
-                                           int wm, int wn) {
-    for_each_quad(wm, wn, [&](int mi, int ni, int g4, int row, int col) {
-        if (row < rows_valid && col < cols_valid) {
-            const f32x16& a = acc[mi][ni];
-            u32x2 v;
-            v.x = pack_bf16x2(a[4 * g4 + 0], a[4 * g4 + 1]);
-            v.y = pack_bf16x2(a[4 * g4 + 2], a[4 * g4 + 3]);
-            *(u32x2*)(out + (int64_t)(row_start + row) * ld + col_start + col) = v;
-        }
-    });
+            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
 }
 
 // ---- operation (2): Y = X W + S' B ---------------------------------------------------------------
-__global__ void __launch_bounds__(NTHREADS, 1) fwd_gemm_kernel(FwdGemmArgs p) {
+__global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int tm, tn;
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
@@ -174,47 +306,57 @@ __global__ void __launch_bounds__(NTHREADS, 1) fwd_gemm_kernel(FwdGemmArgs p) {
     const lora_bf16* Xt = p.X + (int64_t)rt.row_start * p.K;
     const lora_bf16* Wt = p.W + (int64_t)n0 * p.K;
 
-    f32x16 acc[4][2];
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+    f32x16 acc[4][4];
+    zero_acc(acc);
 
-    RowSlabRegs rx, rw;
     const int nk = p.K / BK;
-    load_row_slab(rx, Xt, p.K, rt.rows, 0, 8);
-    load_row_slab(rw, Wt, p.K, cols_valid, 0, 8);
-    store_row_slab(rx, smem);
-    store_row_slab(rw, smem + TILE_BYTES);
+    const uint32_t lds0 = lds_addr_of(smem);
+    const FragLanes fl = frag_lanes();
+    const int tok_org = wm * 128 * 128, out_org = TILE_BYTES + wn * 128 * 128;
+    const SlabLanes sx = row_slab_lanes(p.K, rt.rows, 8), sw = row_slab_lanes(p.K, cols_valid, 8);
+    const SlabLanes ss = row_slab_lanes(p.r, rt.rows, p.r >> 3), sb = row_slab_lanes(p.r, cols_valid, p.r >> 3);
+    load_slab(lds0, Xt, sx);
+    load_slab(lds0 + TILE_BYTES, Wt, sw);
+    wait_slab_loads();
     __syncthreads();
+    Frags f0, f1;
+    read_frags<false>(f0, smem + tok_org, smem + out_org, fl, fl.row_off[0], 0);
+    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
     for (int kt = 0; kt < nk; ++kt) {
-        char* cur = smem + (kt & 1) * STAGE_BYTES;
-        char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
-        if (kt + 1 < nk) {
-            load_row_slab(rx, Xt, p.K, rt.rows, (kt + 1) * BK, 8);
-            load_row_slab(rw, Wt, p.K, cols_valid, (kt + 1) * BK, 8);
-        } else {
-            // the LoRA step rides as one more slab: token operand S' [rows, r], out operand B [N, r]
-            load_row_slab(rx, p.S + (int64_t)rt.row_start * p.r, p.r, rt.rows, 0, p.r >> 3);
-            load_row_slab(rw, p.B + (int64_t)rt.g * p.N * p.r + (int64_t)n0 * p.r, p.r, cols_valid, 0,
-                          p.r >> 3);
+        const int cur = (kt & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
+        NextSlabs nx;
+        nx.valid = true;
+        nx.lds_tok = lds0 + nxt + wave_lds;
+        nx.lds_out = lds0 + nxt + TILE_BYTES + wave_lds;
+        // after the last base slab the LoRA step rides as one more slab: token operand S' [rows, r],
+        // out operand B [N, r]
+        const bool lora = kt + 1 == nk;
+        nx.src_tok = lora ? (const char*)(p.S + (int64_t)rt.row_start * p.r) : (const char*)(Xt + (kt + 1) * BK);
+        nx.src_out = lora ? (const char*)(p.B + ((int64_t)rt.g * p.N + n0) * p.r) : (const char*)(Wt + (kt + 1) * BK);
+#pragma unroll
+        for (int i = 0; i < PASSES; ++i) {
+            nx.lanes_tok.off[i] = lora ? ss.off[i] : sx.off[i];
+            nx.lanes_out.off[i] = lora ? sb.off[i] : sw.off[i];
         }
-        mma_slab<false>(acc, cur, cur + TILE_BYTES, wm, wn, BK / 16);
-        store_row_slab(rx, nxt);
-        store_row_slab(rw, nxt + TILE_BYTES);
-        __syncthreads();
+        slab_step<false>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
+                         smem + nxt + out_org, fl, nx);
     }
     {
-        const char* cur = smem + (nk & 1) * STAGE_BYTES;
-        mma_slab<false>(acc, cur, cur + TILE_BYTES, wm, wn, p.r / 16);
+        const int lo = (nk & 1) * STAGE_BYTES;         // the stage that holds the LoRA slab
+        mma_frags<0, 4>(acc, f0);
+        const int l = threadIdx.x & 63;
+#pragma unroll 1
+        for (int kk = 1; kk < p.r / 16; ++kk) {
+            Frags f;
+            read_frags<false>(f, smem + lo + tok_org, smem + lo + out_org, fl, tile_off(l & 31, 2 * kk + (l >> 5), 8), 0);
+            mma_frags<0, 4>(acc, f);
+        }
     }
     store_tile(acc, p.Y, p.N, rt.row_start, rt.rows, n0, cols_valid, wm, wn);
 }
 
 // ---- operation (5): dX = dY W^T + mask*q*(dS A^T) ------------------------------------------------
-__global__ void __launch_bounds__(NTHREADS, 1) bwd_dx_kernel(DxGemmArgs p) {
+__global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int tm, tn;
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
@@ -224,69 +366,86 @@ __global__ void __launch_bounds__(NTHREADS, 1) bwd_dx_kernel(DxGemmArgs p) {
     const int cols_valid = min(BN, p.K - j0);
     const int w = threadIdx.x >> 6, wm = w & 1, wn = w >> 1;
 
-    f32x16 acc[4][2];
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+    f32x16 acc[4][4];
+    zero_acc(acc);
 
-    RowSlabRegs rd, rw;
     const lora_bf16* dYt = p.dY + (int64_t)rt.row_start * p.N;
     const lora_bf16* Wt = p.W + j0;
+    const uint32_t lds0 = lds_addr_of(smem);
+    const FragLanes fl = frag_lanes();
+    const int tok_org = wm * 128 * 128, out_org = TILE_BYTES + wn * 128 * 2;
+    const SlabLanes sd = row_slab_lanes(p.N, rt.rows, 8), sw = col_slab_lanes(p.K, BK, cols_valid);
 
     // LoRA step first: acc = dS A^T, then the mask and q are applied to the accumulators and the
     // base-gradient contraction continues on top of them.
-    load_row_slab(rd, p.dS + (int64_t)rt.row_start * p.r, p.r, rt.rows, 0, p.r >> 3);
-    load_col_slab(rw, p.A + (int64_t)rt.g * p.r * p.K + j0, p.K, p.r, 0, cols_valid);
-    store_row_slab(rd, smem + STAGE_BYTES);
-    store_col_slab(rw, smem + STAGE_BYTES + TILE_BYTES);
-    load_row_slab(rd, dYt, p.N, rt.rows, 0, 8);
-    load_col_slab(rw, Wt, p.K, BK, 0, cols_valid);
-    __syncthreads();
-    mma_slab<true>(acc, smem + STAGE_BYTES, smem + STAGE_BYTES + TILE_BYTES, wm, wn, p.r / 16);
     {
+        const SlabLanes ss = row_slab_lanes(p.r, rt.rows, p.r >> 3), sa = col_slab_lanes(p.K, p.r, cols_valid);
+        load_slab(lds0 + STAGE_BYTES, p.dS + (int64_t)rt.row_start * p.r, ss);
+        load_slab(lds0 + STAGE_BYTES + TILE_BYTES, p.A + (int64_t)rt.g * p.r * p.K + j0, sa);
+    }
+    load_slab(lds0, dYt, sd);
+    load_slab(lds0 + TILE_BYTES, Wt, sw);
+    wait_slab_loads();
+    __syncthreads();
+    {
+        // one 32x32 block at a time: t = dS A^T on a fresh accumulator, masked and scaled, becomes the
+        // block's starting value.  The hash of a block overlaps the MFMAs of the next one.
         const uint32_t T = p.tb.T[rt.g];
         const float q = p.tb.q[rt.g];
         const uint32_t k0 = p.tb.k0[rt.g], k1 = p.tb.k1[rt.g];
         const int l = threadIdx.x & 63;
+        const int nkk = p.r / 16;
+        const char* lds_tok = smem + STAGE_BYTES + tok_org;
+        const char* lds_out = smem + STAGE_BYTES + out_org;
+        const uint32_t cp0 = (uint32_t)(j0 + wn * 128 + 4 * (l >> 5)) >> 1;     // this lane's first column pair
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi) {
             const int row = wm * 128 + mi * 32 + (l & 31);
             const RowKey rk = row_key(k0, k1, (uint32_t)(rt.local_row0 + row));
+            const uint32_t x0 = rk.a + cp0 * kGold;
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
+            for (int ni = 0; ni < 4; ++ni) {
+                f32x16 t;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) t[i] = 0.f;
+#pragma unroll 1
+                for (int kk = 0; kk < nkk; ++kk) {
+                    const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni & 1][0] + kk * 8192 + (ni >> 1) * 128);
+                    const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni & 1][1] + kk * 8192 + (ni >> 1) * 128);
+                    const bf16x8 ft = __builtin_bit_cast(
+                        bf16x8, *(const u32x4*)(lds_tok + tile_off(l & 31, 2 * kk + (l >> 5), 8) + mi * 4096));
+                    t = LF_MFMA(join_tr(lo, hi), ft, t);
+                }
 #pragma unroll
                 for (int g4 = 0; g4 < 4; ++g4) {
-                    const int col = j0 + wn * 64 + ni * 32 + 8 * g4 + 4 * (l >> 5);
-                    const uint32_t w0 = hash_word(rk, (uint32_t)(col >> 1));
-                    const uint32_t w1 = hash_word(rk, (uint32_t)(col >> 1) + 1);
+                    // columns ni*32 + 8*g4 + {0..3} past the lane's first column: pairs (ni*16 + 4*g4) + {0, 1}
+                    const uint32_t w0 = hash_word_at(rk, x0 + (uint32_t)(ni * 16 + 4 * g4) * kGold);
+                    const uint32_t w1 = hash_word_at(rk, x0 + (uint32_t)(ni * 16 + 4 * g4 + 1) * kGold);
                     f32x16& a = acc[mi][ni];
-                    a[4 * g4 + 0] = (w0 & 0xFFFFu) >= T ? a[4 * g4 + 0] * q : 0.f;
-                    a[4 * g4 + 1] = (w0 >> 16) >= T ? a[4 * g4 + 1] * q : 0.f;
-                    a[4 * g4 + 2] = (w1 & 0xFFFFu) >= T ? a[4 * g4 + 2] * q : 0.f;
-                    a[4 * g4 + 3] = (w1 >> 16) >= T ? a[4 * g4 + 3] * q : 0.f;
+                    a[4 * g4 + 0] = (w0 & 0xFFFFu) >= T ? t[4 * g4 + 0] * q : 0.f;
+                    a[4 * g4 + 1] = (w0 >> 16) >= T ? t[4 * g4 + 1] * q : 0.f;
+                    a[4 * g4 + 2] = (w1 & 0xFFFFu) >= T ? t[4 * g4 + 2] * q : 0.f;
+                    a[4 * g4 + 3] = (w1 >> 16) >= T ? t[4 * g4 + 3] * q : 0.f;
                 }
+                asm volatile("" : "+a"(acc[mi][ni]));    // the block is final here: nothing sinks past
+            }
         }
     }
-    store_row_slab(rd, smem);
-    store_col_slab(rw, smem + TILE_BYTES);
-    __syncthreads();
+    __syncthreads();                                  // every wave is done with the LoRA slab in stage 1
     const int nk = p.N / BK;
+    Frags f0, f1;
+    read_frags<true>(f0, smem + tok_org, smem + out_org, fl, fl.row_off[0], 0);
+    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
     for (int kt = 0; kt < nk; ++kt) {
-        char* cur = smem + (kt & 1) * STAGE_BYTES;
-        char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
-        if (kt + 1 < nk) {
-            load_row_slab(rd, dYt, p.N, rt.rows, (kt + 1) * BK, 8);
-            load_col_slab(rw, Wt + (int64_t)(kt + 1) * BK * p.K, p.K, BK, 0, cols_valid);
-        }
-        mma_slab<true>(acc, cur, cur + TILE_BYTES, wm, wn, BK / 16);
-        if (kt + 1 < nk) {
-            store_row_slab(rd, nxt);
-            store_col_slab(rw, nxt + TILE_BYTES);
-        }
-        __syncthreads();
+        const int cur = (kt & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
+        NextSlabs nx;
+        nx.valid = kt + 1 < nk;
+        nx.lds_tok = lds0 + nxt + wave_lds;
+        nx.lds_out = lds0 + nxt + TILE_BYTES + wave_lds;
+        nx.src_tok = (const char*)(dYt + (kt + 1) * BK); nx.lanes_tok = sd;
+        nx.src_out = (const char*)(Wt + (int64_t)(kt + 1) * BK * p.K); nx.lanes_out = sw;
+        slab_step<true>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
+                        smem + nxt + out_org, fl, nx);
     }
     store_tile(acc, p.dX, p.K, rt.row_start, rt.rows, j0, cols_valid, wm, wn);
 }
