@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c2", help="c1..c5 (default c2, the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unfused", action="store_true",
+                    help="time the unfused multi-kernel baseline instead of the fused path (comparison runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 1 GiB device copy 10 times (reference reading for HBM byte counters)")
     args = ap.parse_args()
@@ -83,9 +85,21 @@ def main():
                   s=[L.s] * L.G, p=[L.p] * L.G)
         state.append(st)
 
+    if args.unfused:
+        for st in state:
+            assert st["L"].G == 1, "the unfused baseline is single-adapter"
+            st["uws"] = binding.unfused_workspace(st["L"].M, st["L"].K, st["L"].N, st["L"].r, dev)
+            st["A1"], st["B1"] = st["A"][0].contiguous(), st["B"][0].contiguous()
+            st["dX"] = torch.empty((st["L"].M, st["L"].K), dtype=torch.bfloat16, device=dev)
+
     def step():
         for st in state:
             L = st["L"]
+            if args.unfused:
+                binding.lora_unfused_fwd(st["X"], st["W"], st["A1"], st["B1"], L.s, L.p, L.seeds[0], st["uws"], Y=st["Y"])
+                binding.lora_unfused_bwd(st["W"], st["A1"], st["B1"], st["dY"], L.s, L.p, L.seeds[0], st["uws"],
+                                         dX=st["dX"], dA=st["dA"][0], dB=st["dB"][0])
+                continue
             binding.multi_lora_fwd(st["X"], st["W"], st["A"], st["B"], L.seg_offsets, st["s"], st["p"], L.seeds,
                                    Y=st["Y"], S=st["S"])
             st["dX"] = binding.multi_lora_bwd(st["X"], st["W"], st["A"], st["B"], st["S"], st["dY"], L.seg_offsets,
@@ -106,6 +120,14 @@ def main():
     tokens = state[0]["L"].M                    # the layers of one configuration share the token batch
     fused_bytes = sum(st["L"].fused_bytes for st in state)
     tflops = flops / (ms_per_step * 1e-3) / 1e12
+
+    if args.unfused:
+        print(json.dumps({"metric": "unfused multi-kernel LoRA linear fwd+bwd (baseline for comparison)",
+                          "value": round(tflops, 2), "unit": "TFLOP/s", "ms_per_step": round(ms_per_step, 4),
+                          "steps": args.steps, "warmup": args.warmup, "config": {"workload": args.workload},
+                          "tokens_per_s": round(tokens / (ms_per_step * 1e-3), 1),
+                          "algorithmic_hbm_bytes_per_token": round(sum(st["L"].unfused_bytes for st in state) / tokens, 1)}))
+        return
 
     # per-kernel durations: same steps again with HIP events around every launch (on the launch stream)
     binding.profile_begin()

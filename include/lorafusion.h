@@ -127,6 +127,22 @@ typedef enum {
 lora_status lora_profile_begin(void);
 lora_status lora_profile_end(float* ms_total, int32_t* launches);
 
+/* Unfused multi-kernel baseline (one adapter, M > 0): the operator-by-operator sequence of the
+ * paper's Section 3.1 / Figure 4 - dropout, X^ A, S B, scaling, X W, add, and the mirrored backward -
+ * with every intermediate materialised in `workspace` (device, 256-byte aligned, at least
+ * lora_unfused_workspace_bytes()).  It exists so that the fused path's HBM traffic and time can be
+ * measured against it.  lora_unfused_bwd consumes the dropped input and S that lora_unfused_fwd left
+ * in the same workspace (pass the same s, p, seed); results equal the fused entry points' up to
+ * rounding of the extra bf16 intermediates.  dA, dB are overwritten. */
+size_t lora_unfused_workspace_bytes(int64_t M, int64_t K, int64_t N, int32_t r);
+lora_status lora_unfused_fwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                             int64_t M, int64_t K, int64_t N, int32_t r, float s, float p, uint64_t seed,
+                             lora_bf16* Y, void* workspace, size_t workspace_bytes, lora_stream stream);
+lora_status lora_unfused_bwd(const lora_bf16* W, const lora_bf16* A, const lora_bf16* B, const lora_bf16* dY,
+                             int64_t M, int64_t K, int64_t N, int32_t r, float s, float p, uint64_t seed,
+                             lora_bf16* dX, float* dA, float* dB, void* workspace, size_t workspace_bytes,
+                             lora_stream stream);
+
 const char* lora_status_string(lora_status st);
 int lora_version(void);
 

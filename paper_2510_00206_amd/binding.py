@@ -45,11 +45,12 @@ def load_library() -> C.CDLL:
     lib.lora_status_string.argtypes = [C.c_int]
     lib.lora_status_string.restype = C.c_char_p
     lib.lora_version.restype = C.c_int
-    if hasattr(lib, "lora_unfused_fwd"):
-        lib.lora_unfused_workspace_bytes.argtypes = [I64, I64, I64, I32]
-        lib.lora_unfused_workspace_bytes.restype = SZ
-        lib.lora_unfused_fwd.argtypes = [P, P, P, P, I64, I64, I64, I32, F, F, U64, P, P, SZ, P]
-        lib.lora_unfused_bwd.argtypes = [P, P, P, P, P, I64, I64, I64, I32, F, F, U64, P, P, P, P, SZ, P]
+    lib.lora_unfused_workspace_bytes.argtypes = [I64, I64, I64, I32]
+    lib.lora_unfused_workspace_bytes.restype = SZ
+    lib.lora_unfused_fwd.argtypes = [P, P, P, P, I64, I64, I64, I32, F, F, U64, P, P, SZ, P]
+    lib.lora_unfused_bwd.argtypes = [P, P, P, P, I64, I64, I64, I32, F, F, U64, P, P, P, P, SZ, P]
+    lib.lora_unfused_fwd.restype = C.c_int
+    lib.lora_unfused_bwd.restype = C.c_int
     lib.lora_profile_end.argtypes = [C.POINTER(F), C.POINTER(I32)]
     for f in ("lora_fwd", "lora_bwd", "multi_lora_fwd", "multi_lora_bwd", "lora_debug_mask",
               "lora_profile_begin", "lora_profile_end"):
@@ -170,3 +171,32 @@ def profile_end():
     ms, cnt = (C.c_float * n)(), (C.c_int32 * n)()
     _check(load_library().lora_profile_end(ms, cnt))
     return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(PROF_KERNELS)}
+
+
+def unfused_workspace(M, K, N, r, device="cuda"):
+    n = int(load_library().lora_unfused_workspace_bytes(M, K, N, r))
+    if n == 0:
+        raise LoraError(7)
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def lora_unfused_fwd(X, W, A, B, s, p, seed, workspace, Y=None):
+    """Unfused baseline forward: Y [M,N]; the dropped input and S stay in `workspace` for the backward."""
+    M, K = X.shape
+    N, r = B.shape
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device) if Y is None else Y
+    _check(load_library().lora_unfused_fwd(_ptr(X), _ptr(W), _ptr(A), _ptr(B), M, K, N, r, s, p, seed, _ptr(Y),
+                                           _ptr(workspace), workspace.numel(), _stream()))
+    return Y
+
+
+def lora_unfused_bwd(W, A, B, dY, s, p, seed, workspace, dX=None, dA=None, dB=None):
+    """Unfused baseline backward (after lora_unfused_fwd on the same workspace): dX, dA, dB."""
+    M, N = dY.shape
+    r, K = A.shape
+    dX = torch.empty((M, K), dtype=torch.bfloat16, device=dY.device) if dX is None else dX
+    dA = torch.empty((r, K), dtype=torch.float32, device=dY.device) if dA is None else dA
+    dB = torch.empty((N, r), dtype=torch.float32, device=dY.device) if dB is None else dB
+    _check(load_library().lora_unfused_bwd(_ptr(W), _ptr(A), _ptr(B), _ptr(dY), M, K, N, r, s, p, seed,
+                                           _ptr(dX), _ptr(dA), _ptr(dB), _ptr(workspace), workspace.numel(), _stream()))
+    return dX, dA, dB

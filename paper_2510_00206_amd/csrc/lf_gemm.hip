@@ -313,10 +313,20 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     const uint32_t lds0 = lds_addr_of(smem);
     const FragLanes fl = frag_lanes();
     const int tok_org = wm * 128 * 128, out_org = TILE_BYTES + wn * 128 * 128;
+    // p.r == 0 (no LoRA slab) and p.K == 0 (LoRA slab only) serve the unfused baseline's plain GEMMs.
+    const bool has_lora = p.r > 0;
+    const int rr = has_lora ? p.r : 16;
     const SlabLanes sx = row_slab_lanes(p.K, rt.rows, 8), sw = row_slab_lanes(p.K, cols_valid, 8);
-    const SlabLanes ss = row_slab_lanes(p.r, rt.rows, p.r >> 3), sb = row_slab_lanes(p.r, cols_valid, p.r >> 3);
-    load_slab(lds0, Xt, sx);
-    load_slab(lds0 + TILE_BYTES, Wt, sw);
+    const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
+    const lora_bf16* Ssrc = p.S + (int64_t)rt.row_start * p.r;
+    const lora_bf16* Bsrc = p.B + ((int64_t)rt.g * p.N + n0) * p.r;
+    if (nk > 0) {
+        load_slab(lds0, Xt, sx);
+        load_slab(lds0 + TILE_BYTES, Wt, sw);
+    } else {
+        load_slab(lds0, Ssrc, ss);
+        load_slab(lds0 + TILE_BYTES, Bsrc, sb);
+    }
     wait_slab_loads();
     __syncthreads();
     Frags f0, f1;
@@ -325,14 +335,14 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = (kt & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
         NextSlabs nx;
-        nx.valid = true;
-        nx.lds_tok = lds0 + nxt + wave_lds;
-        nx.lds_out = lds0 + nxt + TILE_BYTES + wave_lds;
         // after the last base slab the LoRA step rides as one more slab: token operand S' [rows, r],
         // out operand B [N, r]
         const bool lora = kt + 1 == nk;
-        nx.src_tok = lora ? (const char*)(p.S + (int64_t)rt.row_start * p.r) : (const char*)(Xt + (kt + 1) * BK);
-        nx.src_out = lora ? (const char*)(p.B + ((int64_t)rt.g * p.N + n0) * p.r) : (const char*)(Wt + (kt + 1) * BK);
+        nx.valid = !lora || has_lora;
+        nx.lds_tok = lds0 + nxt + wave_lds;
+        nx.lds_out = lds0 + nxt + TILE_BYTES + wave_lds;
+        nx.src_tok = lora ? (const char*)Ssrc : (const char*)(Xt + (kt + 1) * BK);
+        nx.src_out = lora ? (const char*)Bsrc : (const char*)(Wt + (kt + 1) * BK);
 #pragma unroll
         for (int i = 0; i < PASSES; ++i) {
             nx.lanes_tok.off[i] = lora ? ss.off[i] : sx.off[i];
@@ -341,7 +351,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
         slab_step<false>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
                          smem + nxt + out_org, fl, nx);
     }
-    {
+    if (has_lora) {
         const int lo = (nk & 1) * STAGE_BYTES;         // the stage that holds the LoRA slab
         mma_frags<0, 4>(acc, f0);
         const int l = threadIdx.x & 63;
@@ -378,16 +388,20 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
 
     // LoRA step first: acc = dS A^T, then the mask and q are applied to the accumulators and the
     // base-gradient contraction continues on top of them.
-    {
+    // p.r == 0 (no LoRA term) and p.N == 0 (LoRA term only) serve the unfused baseline's plain GEMMs.
+    const int nk = p.N / BK;
+    if (p.r > 0) {
         const SlabLanes ss = row_slab_lanes(p.r, rt.rows, p.r >> 3), sa = col_slab_lanes(p.K, p.r, cols_valid);
         load_slab(lds0 + STAGE_BYTES, p.dS + (int64_t)rt.row_start * p.r, ss);
         load_slab(lds0 + STAGE_BYTES + TILE_BYTES, p.A + (int64_t)rt.g * p.r * p.K + j0, sa);
     }
-    load_slab(lds0, dYt, sd);
-    load_slab(lds0 + TILE_BYTES, Wt, sw);
+    if (nk > 0) {
+        load_slab(lds0, dYt, sd);
+        load_slab(lds0 + TILE_BYTES, Wt, sw);
+    }
     wait_slab_loads();
     __syncthreads();
-    {
+    if (p.r > 0) {
         // one 32x32 block at a time: t = dS A^T on a fresh accumulator, masked and scaled, becomes the
         // block's starting value.  The hash of a block overlaps the MFMAs of the next one.
         const uint32_t T = p.tb.T[rt.g];
@@ -432,9 +446,8 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
         }
     }
     __syncthreads();                                  // every wave is done with the LoRA slab in stage 1
-    const int nk = p.N / BK;
     Frags f0, f1;
-    read_frags<true>(f0, smem + tok_org, smem + out_org, fl, fl.row_off[0], 0);
+    if (nk > 0) read_frags<true>(f0, smem + tok_org, smem + out_org, fl, fl.row_off[0], 0);
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = (kt & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;

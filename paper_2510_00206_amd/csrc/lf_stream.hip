@@ -43,6 +43,8 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     const int t = threadIdx.x, l = t & 63, w = t >> 6;
     const int g = rt.g;
     const uint32_t T = p.tb.T[g], hk0 = p.tb.k0[g], hk1 = p.tb.k1[g];
+    // either output may be switched off (null pointer): the unfused baseline runs them as separate passes
+    const bool do_red = p.part_out != nullptr, do_ds = !IS_DA && p.part_ds != nullptr;
 
     if (!IS_DA) {
         // B chunk [cols_valid, r] of adapter g -> LDS once (rows past the end are zero)
@@ -107,6 +109,7 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
         if (step + 1 < nsteps) load_step(step + 1);
 
         // reduction over the step's 64 rows: this wave owns panel columns [64w, 64w+64)
+        if (do_red)
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
             const int r0 = kk * 32 + 8 * (l >> 4);
@@ -123,7 +126,7 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
             }
         }
 
-        if (!IS_DA) {
+        if (do_ds) {
             // dS for the step's rows over this panel's columns: wave = (16-row block, column half)
             const int rb = w & 3, kh = w >> 2;
             f32x4 ads[CB];
@@ -161,6 +164,7 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     }
 
     // partial dB [tile][n][c] or dA [tile][c][j] of this panel
+    if (do_red)
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
         const int colb = w * 64 + jb * 16;
@@ -273,7 +277,9 @@ __global__ void __launch_bounds__(256) finalize_da_kernel(FinalizeArgs p) {
 }
 
 hipError_t launch_finalize_ds_db(const FinalizeArgs& a, hipStream_t st) {
-    const int64_t n_ds = (int64_t)a.M * (a.r >> 2), n_db = (int64_t)a.tb.G * a.N * (a.r >> 2);
+    const int64_t n_ds = a.part_ds ? (int64_t)a.M * (a.r >> 2) : 0;
+    const int64_t n_db = a.part_db ? (int64_t)a.tb.G * a.N * (a.r >> 2) : 0;
+    if (n_ds + n_db == 0) return hipSuccess;
     const int blocks_ds = (int)((n_ds + 255) / 256), blocks_db = (int)((n_db + 255) / 256);
     hipLaunchKernelGGL(finalize_ds_db_kernel, dim3(blocks_ds + blocks_db), dim3(256), 0, st, a, blocks_ds);
     return hipGetLastError();

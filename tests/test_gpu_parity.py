@@ -151,3 +151,20 @@ def test_error_paths_on_gpu():
         binding.lora_bwd(X, W, A[0].contiguous(), B[0].contiguous(), S, dY, 1.0, 0.1, 1, workspace=small)
     assert e.value.status == 6
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("shape", [(256, 1024, 1024, 16, 2.0, 0.1), (777, 576, 832, 32, 0.5, 0.25),
+                                   (520, 1088, 640, 64, 0.5, 0.1)], ids=lambda s: "x".join(str(v) for v in s[:4]))
+def test_unfused_baseline_parity(shape):
+    """The op-by-op baseline computes the same layer (its extra bf16 intermediates stay inside the bar)."""
+    M, K, N, r, s, p = shape
+    L = workloads.custom_layer(M, K, N, r, s, p, cfg=7)
+    print(f"unfused {L}", flush=True)
+    X, W, A, B, dY = workloads.make_inputs(L)
+    Xg, Wg, Ag, Bg, dYg = (t.cuda() for t in (X, W, A[0].contiguous(), B[0].contiguous(), dY))
+    ws = binding.unfused_workspace(M, K, N, r)
+    Y = binding.lora_unfused_fwd(Xg, Wg, Ag, Bg, s, p, L.seeds[0], ws)
+    dX, dA, dB = binding.lora_unfused_bwd(Wg, Ag, Bg, dYg, s, p, L.seeds[0], ws)
+    torch.cuda.synchronize()
+    ref = run_oracle(L, X, W, A, B, dY)
+    compare(dict(Y=Y, dX=dX, dA=dA[None], dB=dB[None]), ref, label=f"unfused {shape}")
