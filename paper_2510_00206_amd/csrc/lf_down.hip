@@ -38,32 +38,38 @@ __global__ void __launch_bounds__(DOWN_WAVES * 64) down_kernel(DownArgs p) {
         for (int cb = 0; cb < CB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int nchunks = p.K >> 5;
-    u32x4 xv[2], xn[2], av[CB], an[CB];
-    auto load = [&](u32x4 (&x)[2], u32x4 (&a)[CB], int kc) {
+    // each wave walks its 32-column chunks (w, w + 8, ...) with loads running DEPTH chunks ahead
+    constexpr int DEPTH = CB == 1 ? 4 : 2;
+    struct ChunkRegs { u32x4 x[2], a[CB]; };
+    ChunkRegs ring[DEPTH];
+    auto load = [&](ChunkRegs& c, int kc) {
         const int col = kc * 32 + 8 * (l >> 4);
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) x[rb] = *(const u32x4*)(xrow[rb] + col);
+        for (int rb = 0; rb < 2; ++rb) c.x[rb] = *(const u32x4*)(xrow[rb] + col);
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) a[cb] = *(const u32x4*)(Ag + (int64_t)(cb * 16 + (l & 15)) * p.K + col);
+        for (int cb = 0; cb < CB; ++cb) c.a[cb] = *(const u32x4*)(Ag + (int64_t)(cb * 16 + (l & 15)) * p.K + col);
     };
-    int kc = w;
-    if (kc < nchunks) load(xv, av, kc);
-    for (; kc < nchunks; kc += DOWN_WAVES) {
-        const bool more = kc + DOWN_WAVES < nchunks;
-        if (more) load(xn, an, kc + DOWN_WAVES);
+    auto consume = [&](const ChunkRegs& c, int kc) {
         const uint32_t col = (uint32_t)(kc * 32 + 8 * (l >> 4));
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
-            const bf16x8 xf = __builtin_bit_cast(bf16x8, mask8(xv[rb], rk[rb], col, T));
+            const bf16x8 xf = __builtin_bit_cast(bf16x8, mask8(c.x[rb], rk[rb], col, T));
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
-                acc[rb][cb] = LF_MFMA16(__builtin_bit_cast(bf16x8, av[cb]), xf, acc[rb][cb]);
+                acc[rb][cb] = LF_MFMA16(__builtin_bit_cast(bf16x8, c.a[cb]), xf, acc[rb][cb]);
         }
-        if (more) {
+    };
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb) xv[rb] = xn[rb];
+    for (int d = 0; d < DEPTH; ++d)
+        if (w + d * DOWN_WAVES < nchunks) load(ring[d], w + d * DOWN_WAVES);
+    for (int kc = w; kc < nchunks; kc += DEPTH * DOWN_WAVES) {
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) av[cb] = an[cb];
+        for (int d = 0; d < DEPTH; ++d) {
+            const int k = kc + d * DOWN_WAVES;
+            if (k < nchunks) {
+                consume(ring[d], k);
+                if (k + DEPTH * DOWN_WAVES < nchunks) load(ring[d], k + DEPTH * DOWN_WAVES);
+            }
         }
     }
 #pragma unroll

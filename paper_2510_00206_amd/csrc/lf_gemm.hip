@@ -69,7 +69,7 @@ __device__ __forceinline__ SlabLanes row_slab_lanes(int64_t ld, int rows_valid, 
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
         const int row = 8 * (NWAVES * i + w) + (l >> 3);
-        const int chunk = min((l & 7) ^ swz(row), nchunk_valid - 1);
+        const int chunk = min((l & 7) ^ row_slab_swz(row), nchunk_valid - 1);
         s.off[i] = (uint32_t)((min(row, rows_valid - 1) * ld + chunk * 8) * 2);
     }
     return s;
@@ -83,7 +83,7 @@ __device__ __forceinline__ SlabLanes col_slab_lanes(int64_t ld, int rows_valid, 
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
         const int row = 2 * (NWAVES * i + w) + (l >> 5);
-        const int chunk = min((l & 31) ^ swz(row), (cols_valid >> 3) - 1);
+        const int chunk = min((l & 31) ^ col_slab_swz(row), (cols_valid >> 3) - 1);
         s.off[i] = (uint32_t)((min(row, rows_valid - 1) * ld + chunk * 8) * 2);
     }
     return s;
@@ -104,20 +104,20 @@ __device__ __forceinline__ void load_slab(uint32_t lds_slab_addr, const lora_bf1
 //  row slab: 32 tile rows x 16 contraction elements, lane l holds row (l & 31), elements
 //            8*(l >> 5) .. +7 of sub-step kk  -> row_off[kk] (+ 4096 bytes per 32 tile rows)
 //  col slab: 32 output columns x 16 contraction rows through two transposing reads, lane l holds
-//            column (l & 31), rows 16*kk + 8*(l >> 5) + {0..3 | 4..7} -> col_off[ni & 1][half]
-//            (+ 8192 bytes per sub-step kk, + 128 bytes per 64 columns)
-struct FragLanes { int row_off[4]; int col_off[2][2]; };
+//            column (l & 31), rows 16*kk + 8*(l >> 5) + {0..3 | 4..7} -> col_off[ni][half]
+//            (+ 8192 bytes per sub-step kk)
+struct FragLanes { int row_off[4]; int col_off[4][2]; };
 
 __device__ __forceinline__ FragLanes frag_lanes() {
     const int l = threadIdx.x & 63;
     FragLanes f;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) f.row_off[kk] = tile_off(l & 31, 2 * kk + (l >> 5), 8);
+    for (int kk = 0; kk < 4; ++kk) f.row_off[kk] = row_slab_off(l & 31, 2 * kk + (l >> 5));
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
+    for (int ni = 0; ni < 4; ++ni)
 #pragma unroll
         for (int h = 0; h < 2; ++h)
-            f.col_off[ni][h] = tr_off(8 * (l >> 5) + 4 * h, ni * 32 + ((l >> 4) & 1) * 16, l & 15, 32);
+            f.col_off[ni][h] = col_slab_tr_off(8 * (l >> 5) + 4 * h, ni * 32 + ((l >> 4) & 1) * 16, l & 15);
     return f;
 }
 
@@ -131,8 +131,8 @@ __device__ __forceinline__ void read_frags(Frags& f, const char* lds_tok, const 
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
         if (OUT_IS_COL_SLAB) {
-            const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni & 1][0] + col_step + (ni >> 1) * 128);
-            const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni & 1][1] + col_step + (ni >> 1) * 128);
+            const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni][0] + col_step);
+            const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni][1] + col_step);
             f.fo[ni] = join_tr(lo, hi);
         } else {
             f.fo[ni] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_out + row_off_kk + ni * 4096));
@@ -155,7 +155,7 @@ __device__ __forceinline__ void mma_frags(f32x16 (&acc)[4][4], const Frags& f) {
 // What the next slab pair is copied from: two operand slabs of PASSES wave-passes each.
 struct NextSlabs {
     const char* src_tok; const char* src_out;     // workgroup-uniform addresses of the slabs' first elements
-    SlabLanes lanes_tok, lanes_out;
+    const SlabLanes& lanes_tok; const SlabLanes& lanes_out;
     uint32_t lds_tok, lds_out;                    // LDS addresses of the destination slabs (+ this wave's 1024 B)
     bool valid;
 };
@@ -168,49 +168,57 @@ __device__ __forceinline__ void issue_copy(const NextSlabs& nx) {
     else copy16_to_lds(nx.src_out, nx.lanes_out.off[J - PASSES], nx.lds_out + (J - PASSES) * (NWAVES * 1024));
 }
 
-template <bool OUT_IS_COL_SLAB>
-__device__ __forceinline__ void read_frag_pair(Frags& f, int i, const char* lds_tok, const char* lds_out,
+// One operand fragment read of the next sub-step.  Items come in the order the MFMAs need them
+// (MFMA slot s uses out fragment s & 3 and token fragment s >> 2): out0, tok0, out1, out2, out3,
+// tok1, tok2, tok3.
+template <bool OUT_IS_COL_SLAB, int ITEM>
+__device__ __forceinline__ void read_frag_item(Frags& f, const char* lds_tok, const char* lds_out,
                                                const FragLanes& fl, int row_off_kk, int col_step) {
-    if (OUT_IS_COL_SLAB) {
-        const s16x4 lo = lds_read_tr(lds_out, fl.col_off[i & 1][0] + col_step + (i >> 1) * 128);
-        const s16x4 hi = lds_read_tr(lds_out, fl.col_off[i & 1][1] + col_step + (i >> 1) * 128);
+    constexpr bool is_tok = ITEM == 1 || ITEM >= 5;
+    constexpr int i = ITEM == 0 ? 0 : ITEM == 1 ? 0 : ITEM <= 4 ? ITEM - 1 : ITEM - 4;
+    if constexpr (is_tok) {
+        f.ft[i] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_tok + row_off_kk + i * 4096));
+    } else if constexpr (OUT_IS_COL_SLAB) {
+        const s16x4 lo = lds_read_tr(lds_out, fl.col_off[i][0] + col_step);
+        const s16x4 hi = lds_read_tr(lds_out, fl.col_off[i][1] + col_step);
         f.fo[i] = join_tr(lo, hi);
     } else {
         f.fo[i] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_out + row_off_kk + i * 4096));
     }
-    f.ft[i] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_tok + row_off_kk + i * 4096));
 }
 
-// One sub-step of 16 MFMAs in four groups of four; before each group the wave issues a quarter of
-// the next sub-step's fragment reads and COPIES global->LDS copies of the next slab pair, so that
-// LDS reads, copy issue and MFMAs are spread evenly instead of queueing behind one another.
-template <bool OUT_IS_COL_SLAB, int KK_NEXT, int COPY0, int COPIES>
-__device__ __forceinline__ void phase(f32x16 (&acc)[4][4], const Frags& cur, Frags& nxt, const char* lds_tok,
-                                      const char* lds_out, const FragLanes& fl, const NextSlabs& nx) {
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        read_frag_pair<OUT_IS_COL_SLAB>(nxt, g, lds_tok, lds_out, fl, fl.row_off[KK_NEXT], KK_NEXT * 8192);
-        if (COPIES >= 1) {
-            if (g == 0) issue_copy<COPY0 + 0 * COPIES>(nx);
-            if (g == 1) issue_copy<COPY0 + 1 * COPIES>(nx);
-            if (g == 2) issue_copy<COPY0 + 2 * COPIES>(nx);
-            if (g == 3) issue_copy<COPY0 + 3 * COPIES>(nx);
-        }
-        if (COPIES >= 2) {
-            if (g == 0) issue_copy<COPY0 + 0 * COPIES + 1>(nx);
-            if (g == 1) issue_copy<COPY0 + 1 * COPIES + 1>(nx);
-            if (g == 2) issue_copy<COPY0 + 2 * COPIES + 1>(nx);
-            if (g == 3) issue_copy<COPY0 + 3 * COPIES + 1>(nx);
-        }
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) acc[g][ni] = LF_MFMA(cur.fo[ni], cur.ft[g], acc[g][ni]);
-        __builtin_amdgcn_sched_barrier(0);
+// One sub-step: 16 MFMAs, each followed by at most one other instruction group - on even slots a
+// fragment read of the next sub-step, on odd slots a global->LDS copy of the next slab pair - so that
+// every LDS read and every copy is issued while an MFMA executes (a copy or read issued between two
+// groups of MFMAs leaves the matrix pipe idle for its whole issue time).
+// MODE 0: reads of sub-step KK_NEXT + copies; MODE 1: MFMAs only; MODE 2: reads of the next slab's sub-step 0.
+template <bool OUT_IS_COL_SLAB, int KK_NEXT, int COPY0, int COPIES, int SLOT0, int SLOT1, int MODE>
+__device__ __forceinline__ void phase_slots(f32x16 (&acc)[4][4], const Frags& cur, Frags& nxt, const char* lds_tok,
+                                            const char* lds_out, const FragLanes& fl, const NextSlabs& nx) {
+#define LF_SLOT(S)                                                                                        \
+    if constexpr ((S) >= SLOT0 && (S) < SLOT1) {                                                         \
+        acc[(S) >> 2][(S) & 3] = LF_MFMA(cur.fo[(S) & 3], cur.ft[(S) >> 2], acc[(S) >> 2][(S) & 3]);      \
+        if constexpr (MODE == 2) {                                                                        \
+            /* hand-over half: all eight fragment reads of the next slab ride on slots 8..15 */         \
+            if (nx.valid)                                                                                 \
+                read_frag_item<OUT_IS_COL_SLAB, ((S) - 8)>(nxt, lds_tok, lds_out, fl, fl.row_off[0], 0);    \
+        } else if constexpr (MODE == 1) {                                                                 \
+        } else if constexpr (((S) & 1) == 0) {                                                            \
+            read_frag_item<OUT_IS_COL_SLAB, ((S) >> 1)>(nxt, lds_tok, lds_out, fl, fl.row_off[KK_NEXT],     \
+                                                       KK_NEXT * 8192);                                  \
+        } else if constexpr (((S) >> 1) < COPIES) {                                                       \
+            issue_copy<(COPY0 + ((S) >> 1))>(nx);                                                           \
+        }                                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
     }
+    LF_SLOT(0) LF_SLOT(1) LF_SLOT(2) LF_SLOT(3) LF_SLOT(4) LF_SLOT(5) LF_SLOT(6) LF_SLOT(7)
+    LF_SLOT(8) LF_SLOT(9) LF_SLOT(10) LF_SLOT(11) LF_SLOT(12) LF_SLOT(13) LF_SLOT(14) LF_SLOT(15)
+#undef LF_SLOT
 }
 
-// One 64-deep slab pair: sub-steps 0..3, the copies of the next slab pair spread over sub-steps 0..2,
-// and in the middle of sub-step 3 the hand-over (copies landed, workgroup barrier) followed by the
-// first fragment reads of the next slab.  On entry f0 holds the fragments of sub-step 0 of the
+// One 64-deep slab pair: sub-steps 0..3, the 16 copies of the next slab pair spread over sub-steps
+// 0 and 1, and in the middle of sub-step 3 the hand-over (copies landed, workgroup barrier) followed by
+// the first fragment reads of the next slab.  On entry f0 holds the fragments of sub-step 0 of the
 // current slab; on exit it holds those of the next slab.
 template <bool OUT_IS_COL_SLAB>
 __device__ __forceinline__ void slab_step(f32x16 (&acc)[4][4], Frags& f0, Frags& f1, const char* cur_tok,
@@ -218,27 +226,14 @@ __device__ __forceinline__ void slab_step(f32x16 (&acc)[4][4], Frags& f0, Frags&
                                           const FragLanes& fl, const NextSlabs& nx) {
     static_assert(PASSES == 8, "copy schedule below assumes 16 copies per slab pair");
     __builtin_amdgcn_sched_barrier(0);
-    phase<OUT_IS_COL_SLAB, 1, 0, 2>(acc, f0, f1, cur_tok, cur_out, fl, nx);     // copies 0..7
-    phase<OUT_IS_COL_SLAB, 2, 8, 1>(acc, f1, f0, cur_tok, cur_out, fl, nx);     // copies 8..11
-    phase<OUT_IS_COL_SLAB, 3, 12, 1>(acc, f0, f1, cur_tok, cur_out, fl, nx);    // copies 12..15
-    // sub-step 3
-#pragma unroll
-    for (int g = 0; g < 2; ++g)
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) acc[g][ni] = LF_MFMA(f1.fo[ni], f1.ft[g], acc[g][ni]);
-    __builtin_amdgcn_sched_barrier(0);
+    phase_slots<OUT_IS_COL_SLAB, 1, 0, 8, 0, 16, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx);   // copies 0..7
+    phase_slots<OUT_IS_COL_SLAB, 2, 8, 8, 0, 16, 0>(acc, f1, f0, cur_tok, cur_out, fl, nx);   // copies 8..15
+    phase_slots<OUT_IS_COL_SLAB, 3, 0, 0, 0, 16, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx);
+    // sub-step 3: first half, hand-over, second half with the next slab's first fragment reads
+    phase_slots<OUT_IS_COL_SLAB, 0, 0, 0, 0, 8, 1>(acc, f1, f0, cur_tok, cur_out, fl, nx);
     wait_slab_loads();
     __syncthreads();
-#pragma unroll
-    for (int g = 2; g < 4; ++g) {
-        if (nx.valid) {
-            read_frag_pair<OUT_IS_COL_SLAB>(f0, 2 * (g - 2), nxt_tok, nxt_out, fl, fl.row_off[0], 0);
-            read_frag_pair<OUT_IS_COL_SLAB>(f0, 2 * (g - 2) + 1, nxt_tok, nxt_out, fl, fl.row_off[0], 0);
-        }
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) acc[g][ni] = LF_MFMA(f1.fo[ni], f1.ft[g], acc[g][ni]);
-        __builtin_amdgcn_sched_barrier(0);
-    }
+    phase_slots<OUT_IS_COL_SLAB, 0, 0, 0, 8, 16, 2>(acc, f1, f0, nxt_tok, nxt_out, fl, nx);
 }
 
 // A slab with a run-time number of sub-steps (the rank-r LoRA slab: r/16 sub-steps), as one rolled
@@ -250,36 +245,50 @@ __device__ __forceinline__ void mma_slab_rolled(f32x16 (&acc)[4][4], const char*
 #pragma unroll 1
     for (int kk = 0; kk < nkk; ++kk) {
         Frags f;
-        read_frags<OUT_IS_COL_SLAB>(f, lds_tok, lds_out, fl, tile_off(l & 31, 2 * kk + (l >> 5), 8), kk * 8192);
+        read_frags<OUT_IS_COL_SLAB>(f, lds_tok, lds_out, fl, row_slab_off(l & 31, 2 * kk + (l >> 5)), kk * 8192);
         mma_frags<0, 4>(acc, f);
     }
 }
 
 // Accumulator element (mi, ni, i) of lane l is output row  wm*128 + mi*32 + (l & 31)  and output
 // column  wn*128 + ni*32 + 8*(i >> 2) + 4*(l >> 5) + (i & 3)  of the tile: a lane owns groups of four
-// consecutive columns of one row.
+// consecutive columns of one row.  Storing those 8-byte groups directly would touch 32 different
+// rows per instruction; instead each wave transposes its 128x128 bf16 sub-tile through its own 32 KB
+// of the (now idle) slab LDS and writes whole 256-byte row segments, 16 bytes per lane.
+// LDS layout per wave: 128 rows x 32 eight-byte slots, slot index XOR-ed with (row & 31) so that the
+// 32 rows written by one instruction land in 32 different slots.
 __device__ __forceinline__ void store_tile(const f32x16 (&acc)[4][4], lora_bf16* out, int64_t ld,
                                            int row_start, int rows_valid, int col_start, int cols_valid,
-                                           int wm, int wn) {
+                                           int wm, int wn, char* smem) {
     const int l = threadIdx.x & 63;
+    __syncthreads();                                   // every wave is done reading operand slabs
+    char* reg = smem + (threadIdx.x >> 6) * 32768;
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
-        const int row = wm * 128 + mi * 32 + (l & 31);
-        if (row >= rows_valid) continue;
-        lora_bf16* orow = out + (int64_t)(row_start + row) * ld + col_start;
+        const int r = mi * 32 + (l & 31);
 #pragma unroll
         for (int ni = 0; ni < 4; ++ni)
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
-                const int col = wn * 128 + ni * 32 + 8 * g4 + 4 * (l >> 5);
-                if (col < cols_valid) {
-                    const f32x16& a = acc[mi][ni];
-                    u32x2 v;
-                    v.x = pack_bf16x2(a[4 * g4 + 0], a[4 * g4 + 1]);
-                    v.y = pack_bf16x2(a[4 * g4 + 2], a[4 * g4 + 3]);
-                    *(u32x2*)(orow + col) = v;
-                }
+                const f32x16& a = acc[mi][ni];
+                u32x2 v;
+                v.x = pack_bf16x2(a[4 * g4 + 0], a[4 * g4 + 1]);
+                v.y = pack_bf16x2(a[4 * g4 + 2], a[4 * g4 + 3]);
+                const int slot = ni * 8 + 2 * g4 + (l >> 5);
+                *(u32x2*)(reg + r * 256 + ((slot ^ (r & 31)) << 3)) = v;
             }
+    }
+    // LDS operations of one wave complete in order: the reads below see the writes above
+    const int j = l & 15;                              // 16-byte chunk of the row: columns 8j .. 8j+7
+    const bool col_ok = wn * 128 + j * 8 < cols_valid;
+#pragma unroll 8
+    for (int it = 0; it < 32; ++it) {
+        const int r = it * 4 + (l >> 4);
+        u32x4 v = *(const u32x4*)(reg + r * 256 + ((j ^ ((r & 31) >> 1)) << 4));
+        if (r & 1) v = u32x4{v.z, v.w, v.x, v.y};      // odd rows hold the two slots of a chunk swapped
+        const int row = wm * 128 + r;
+        if (col_ok && row < rows_valid)
+            *(u32x4*)(out + (int64_t)(row_start + row) * ld + col_start + wn * 128 + j * 8) = v;
     }
 }
 
@@ -332,22 +341,19 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     Frags f0, f1;
     read_frags<false>(f0, smem + tok_org, smem + out_org, fl, fl.row_off[0], 0);
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
-    for (int kt = 0; kt < nk; ++kt) {
+    for (int kt = 0; kt + 1 < nk; ++kt) {
         const int cur = (kt & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
-        NextSlabs nx;
+        const NextSlabs nx{(const char*)(Xt + (kt + 1) * BK), (const char*)(Wt + (kt + 1) * BK), sx, sw,
+                           lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, true};
+        slab_step<false>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
+                         smem + nxt + out_org, fl, nx);
+    }
+    if (nk > 0) {
         // after the last base slab the LoRA step rides as one more slab: token operand S' [rows, r],
         // out operand B [N, r]
-        const bool lora = kt + 1 == nk;
-        nx.valid = !lora || has_lora;
-        nx.lds_tok = lds0 + nxt + wave_lds;
-        nx.lds_out = lds0 + nxt + TILE_BYTES + wave_lds;
-        nx.src_tok = lora ? (const char*)Ssrc : (const char*)(Xt + (kt + 1) * BK);
-        nx.src_out = lora ? (const char*)Bsrc : (const char*)(Wt + (kt + 1) * BK);
-#pragma unroll
-        for (int i = 0; i < PASSES; ++i) {
-            nx.lanes_tok.off[i] = lora ? ss.off[i] : sx.off[i];
-            nx.lanes_out.off[i] = lora ? sb.off[i] : sw.off[i];
-        }
+        const int cur = ((nk - 1) & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
+        const NextSlabs nx{(const char*)Ssrc, (const char*)Bsrc, ss, sb,
+                           lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, has_lora};
         slab_step<false>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
                          smem + nxt + out_org, fl, nx);
     }
@@ -358,11 +364,11 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
 #pragma unroll 1
         for (int kk = 1; kk < p.r / 16; ++kk) {
             Frags f;
-            read_frags<false>(f, smem + lo + tok_org, smem + lo + out_org, fl, tile_off(l & 31, 2 * kk + (l >> 5), 8), 0);
+            read_frags<false>(f, smem + lo + tok_org, smem + lo + out_org, fl, row_slab_off(l & 31, 2 * kk + (l >> 5)), 0);
             mma_frags<0, 4>(acc, f);
         }
     }
-    store_tile(acc, p.Y, p.N, rt.row_start, rt.rows, n0, cols_valid, wm, wn);
+    store_tile(acc, p.Y, p.N, rt.row_start, rt.rows, n0, cols_valid, wm, wn, smem);
 }
 
 // ---- operation (5): dX = dY W^T + mask*q*(dS A^T) ------------------------------------------------
@@ -424,10 +430,10 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
                 for (int i = 0; i < 16; ++i) t[i] = 0.f;
 #pragma unroll 1
                 for (int kk = 0; kk < nkk; ++kk) {
-                    const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni & 1][0] + kk * 8192 + (ni >> 1) * 128);
-                    const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni & 1][1] + kk * 8192 + (ni >> 1) * 128);
+                    const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni][0] + kk * 8192);
+                    const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni][1] + kk * 8192);
                     const bf16x8 ft = __builtin_bit_cast(
-                        bf16x8, *(const u32x4*)(lds_tok + tile_off(l & 31, 2 * kk + (l >> 5), 8) + mi * 4096));
+                        bf16x8, *(const u32x4*)(lds_tok + row_slab_off(l & 31, 2 * kk + (l >> 5)) + mi * 4096));
                     t = LF_MFMA(join_tr(lo, hi), ft, t);
                 }
 #pragma unroll
@@ -451,16 +457,12 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = (kt & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
-        NextSlabs nx;
-        nx.valid = kt + 1 < nk;
-        nx.lds_tok = lds0 + nxt + wave_lds;
-        nx.lds_out = lds0 + nxt + TILE_BYTES + wave_lds;
-        nx.src_tok = (const char*)(dYt + (kt + 1) * BK); nx.lanes_tok = sd;
-        nx.src_out = (const char*)(Wt + (int64_t)(kt + 1) * BK * p.K); nx.lanes_out = sw;
+        const NextSlabs nx{(const char*)(dYt + (kt + 1) * BK), (const char*)(Wt + (int64_t)(kt + 1) * BK * p.K), sd, sw,
+                           lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, kt + 1 < nk};
         slab_step<true>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
                         smem + nxt + out_org, fl, nx);
     }
-    store_tile(acc, p.dX, p.K, rt.row_start, rt.rows, j0, cols_valid, wm, wn);
+    store_tile(acc, p.dX, p.K, rt.row_start, rt.rows, j0, cols_valid, wm, wn, smem);
 }
 
 // ---- host launchers -------------------------------------------------------------------------------

@@ -26,6 +26,13 @@ __device__ __forceinline__ bf16x8 read_tr_frag(const char* lds, int r0, int c0, 
     return join_tr(lo, hi);
 }
 
+__device__ __forceinline__ bf16x8 read_panel_tr_frag(const char* lds, int r0, int c0) {
+    const int l = threadIdx.x & 63;
+    const s16x4 lo = lds_read_tr(lds, panel_tr_off(r0, c0, l & 15));
+    const s16x4 hi = lds_read_tr(lds, panel_tr_off(r0 + 4, c0, l & 15));
+    return join_tr(lo, hi);
+}
+
 template <int CB, bool IS_DA>   // CB = r/16; IS_DA: operation (4), else operation (3)
 __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -69,45 +76,41 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     const int bchunk = t & 63;                                // this thread's 16-byte chunk of a panel row
     const bool col_ok = bchunk * 8 < cols_valid;
 
-    u32x4 rb_[8], rs_;
-    auto load_step = [&](int step) {
+    struct StepRegs { u32x4 b[8], s; };
+    auto load_step = [&](StepRegs& rg, int step) {
         const int rows_left = rt.rows - step * ST_STEP;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int row = (t >> 6) + 8 * i;
-            rb_[i] = u32x4{0u, 0u, 0u, 0u};
+            rg.b[i] = u32x4{0u, 0u, 0u, 0u};
             if (col_ok && row < rows_left)
-                rb_[i] = *(const u32x4*)(big + (int64_t)(step * ST_STEP + row) * p.C + bchunk * 8);
+                rg.b[i] = *(const u32x4*)(big + (int64_t)(step * ST_STEP + row) * p.C + bchunk * 8);
         }
-        rs_ = u32x4{0u, 0u, 0u, 0u};
+        rg.s = u32x4{0u, 0u, 0u, 0u};
         if (t < ST_STEP * RCH) {
             const int row = t / RCH, ch = t - row * RCH;
-            if (row < rows_left) rs_ = *(const u32x4*)(small_ + (int64_t)(step * ST_STEP + row) * R + ch * 8);
+            if (row < rows_left) rg.s = *(const u32x4*)(small_ + (int64_t)(step * ST_STEP + row) * R + ch * 8);
         }
     };
-    auto store_step = [&](int step) {
+    auto store_step = [&](const StepRegs& rg, int step) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int row = (t >> 6) + 8 * i;
-            u32x4 v = rb_[i];
+            u32x4 v = rg.b[i];
             if (IS_DA) {
                 const RowKey rk = row_key(hk0, hk1, (uint32_t)(rt.local_row0 + step * ST_STEP + row));
                 v = mask8(v, rk, (uint32_t)(c0 + bchunk * 8), T);
             }
-            *(u32x4*)(lds_big + tile_off(row, bchunk, ST_CH16)) = v;
+            *(u32x4*)(lds_big + panel_off(row, bchunk)) = v;
         }
         if (t < ST_STEP * RCH) {
             const int row = t / RCH, ch = t - row * RCH;
-            *(u32x4*)(lds_small + tile_off(row, ch, RCH)) = rs_;
+            *(u32x4*)(lds_small + tile_off(row, ch, RCH)) = rg.s;
         }
     };
 
-    load_step(0);
-    for (int step = 0; step < nsteps; ++step) {
-        store_step(step);
-        __syncthreads();
-        if (step + 1 < nsteps) load_step(step + 1);
-
+    // everything that consumes the step's LDS tiles (ends with the barrier that frees them)
+    auto compute_step = [&](int step) {
         // reduction over the step's 64 rows: this wave owns panel columns [64w, 64w+64)
         if (do_red)
 #pragma unroll
@@ -118,7 +121,7 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
             for (int cb = 0; cb < CB; ++cb) fs[cb] = read_tr_frag(lds_small, r0, cb * 16, RCH);
 #pragma unroll
             for (int jb = 0; jb < 4; ++jb) {
-                const bf16x8 fb = read_tr_frag(lds_big, r0, w * 64 + jb * 16, ST_CH16);
+                const bf16x8 fb = read_panel_tr_frag(lds_big, r0, w * 64 + jb * 16);
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb)
                     acc[jb][cb] = IS_DA ? LF_MFMA16(fb, fs[cb], acc[jb][cb])     // D[j][c]
@@ -135,7 +138,7 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
 #pragma unroll
             for (int kq = 0; kq < 8; ++kq) {
                 const int ncol = kh * 256 + kq * 32;              // panel column of this k-chunk
-                const u32x4 tv = *(const u32x4*)(lds_big + tile_off(rb * 16 + (l & 15), (ncol >> 3) + (l >> 4), ST_CH16));
+                const u32x4 tv = *(const u32x4*)(lds_big + panel_off(rb * 16 + (l & 15), (ncol >> 3) + (l >> 4)));
                 const bf16x8 ft = __builtin_bit_cast(bf16x8, tv);
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) {
@@ -161,6 +164,37 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
             }
         }
         __syncthreads();
+    };
+
+    // loads run two steps ahead of their use (two register sets), so that a step's HBM latency is
+    // covered by two steps of work rather than one; the rank-64 dS+dB variant has no registers to
+    // spare and stays one step ahead
+    constexpr bool TWO_AHEAD = !(CB == 4 && !IS_DA);
+    if constexpr (TWO_AHEAD) {
+        StepRegs ra, rb2;
+        load_step(ra, 0);
+        if (nsteps > 1) load_step(rb2, 1);
+        for (int step = 0; step < nsteps; step += 2) {
+            store_step(ra, step);
+            __syncthreads();
+            if (step + 2 < nsteps) load_step(ra, step + 2);
+            compute_step(step);
+            if (step + 1 < nsteps) {
+                store_step(rb2, step + 1);
+                __syncthreads();
+                if (step + 3 < nsteps) load_step(rb2, step + 3);
+                compute_step(step + 1);
+            }
+        }
+    } else {
+        StepRegs ra;
+        load_step(ra, 0);
+        for (int step = 0; step < nsteps; ++step) {
+            store_step(ra, step);
+            __syncthreads();
+            if (step + 1 < nsteps) load_step(ra, step + 1);
+            compute_step(step);
+        }
     }
 
     // partial dB [tile][n][c] or dA [tile][c][j] of this panel
@@ -236,6 +270,7 @@ __global__ void __launch_bounds__(256) finalize_ds_db_kernel(FinalizeArgs p, int
         const int row = (int)(idx / r4);
         const float s = p.tb.s[segment_of_row(p.tb, row)];
         f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
         for (int ch = 0; ch < p.chunks; ++ch) v += *(const f32x4*)(p.part_ds + ((int64_t)ch * p.M * r4 + idx) * 4);
         u32x2 o;
         o.x = pack_bf16x2(v[0] * s, v[1] * s);
@@ -252,6 +287,7 @@ __global__ void __launch_bounds__(256) finalize_ds_db_kernel(FinalizeArgs p, int
         const int nt = (p.tb.row0[g + 1] - p.tb.row0[g] + kRowTile - 1) / kRowTile;
         if (nt == 0 && p.accumulate) return;
         f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
         for (int tl = tile0; tl < tile0 + nt; ++tl) v += *(const f32x4*)(p.part_db + ((int64_t)tl * per_g + e) * 4);
         f32x4* out = (f32x4*)(p.dB + idx * 4);
         *out = p.accumulate ? *out + v : v;
@@ -270,6 +306,7 @@ __global__ void __launch_bounds__(256) finalize_da_kernel(FinalizeArgs p) {
     const int nt = (p.tb.row0[g + 1] - p.tb.row0[g] + kRowTile - 1) / kRowTile;
     if (nt == 0 && p.accumulate) return;
     f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
     for (int tl = tile0; tl < tile0 + nt; ++tl) v += *(const f32x4*)(p.part_da + ((int64_t)tl * per_g + e) * 4);
     v *= p.tb.q[g];
     f32x4* out = (f32x4*)(p.dA + idx * 4);
