@@ -82,18 +82,34 @@ __device__ __forceinline__ uint32_t hash_word_at(RowKey rk, uint32_t x) {
     return x;
 }
 
-// AND-mask for a packed pair of bf16 (even column in the low half).
-__device__ __forceinline__ uint32_t keep_pair_mask(uint32_t w, uint32_t T) {
-    return ((w & 0xFFFFu) >= T ? 0x0000FFFFu : 0u) | ((w >> 16) >= T ? 0xFFFF0000u : 0u);
+// AND-mask for a packed pair of bf16 (even column in the low half): 0xFFFF in a half iff its
+// 16 hash bits are >= T.  Packed 16-bit arithmetic: saturating (bits - (T-1)) is non-zero iff
+// bits >= T (for T >= 1); min(.,1) * 0xFFFF spreads it over the half.  T == 0 keeps everything.
+struct KeepThreshold { uint32_t tm1_packed; uint32_t keep_all; };
+
+__host__ __device__ __forceinline__ KeepThreshold keep_threshold(uint32_t T) {
+    KeepThreshold k;
+    const uint32_t tm1 = T ? T - 1 : 0xFFFFu;          // T == 0: nothing passes the test, keep_all covers it
+    k.tm1_packed = tm1 | (tm1 << 16);
+    k.keep_all = T ? 0u : 0xFFFFFFFFu;
+    return k;
+}
+
+__device__ __forceinline__ uint32_t keep_pair_mask(uint32_t w, KeepThreshold kt) {
+    typedef __attribute__((ext_vector_type(2))) unsigned short u16x2;
+    const u16x2 d = __builtin_elementwise_sub_sat(__builtin_bit_cast(u16x2, w), __builtin_bit_cast(u16x2, kt.tm1_packed));
+    const u16x2 one = {1, 1}, ffff = {0xFFFF, 0xFFFF};
+    const u16x2 m = __builtin_elementwise_min(d, one) * ffff;
+    return __builtin_bit_cast(uint32_t, m) | kt.keep_all;
 }
 
 // Mask 8 consecutive bf16 (columns col..col+7, col % 8 == 0) held in a 16-byte vector.
-__device__ __forceinline__ u32x4 mask8(u32x4 v, RowKey rk, uint32_t col, uint32_t T) {
-    const uint32_t cp = col >> 1;
-    v.x &= keep_pair_mask(hash_word(rk, cp + 0), T);
-    v.y &= keep_pair_mask(hash_word(rk, cp + 1), T);
-    v.z &= keep_pair_mask(hash_word(rk, cp + 2), T);
-    v.w &= keep_pair_mask(hash_word(rk, cp + 3), T);
+__device__ __forceinline__ u32x4 mask8(u32x4 v, RowKey rk, uint32_t col, KeepThreshold kt) {
+    const uint32_t x = rk.a + (col >> 1) * kGold;      // consecutive column pairs differ by kGold
+    v.x &= keep_pair_mask(hash_word_at(rk, x), kt);
+    v.y &= keep_pair_mask(hash_word_at(rk, x + kGold), kt);
+    v.z &= keep_pair_mask(hash_word_at(rk, x + 2u * kGold), kt);
+    v.w &= keep_pair_mask(hash_word_at(rk, x + 3u * kGold), kt);
     return v;
 }
 

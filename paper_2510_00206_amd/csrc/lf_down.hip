@@ -20,7 +20,7 @@ __global__ void __launch_bounds__(DOWN_WAVES * 64) down_kernel(DownArgs p) {
     if (!find_row_tile(p.tb, DOWN_ROWS, blockIdx.x, rt)) return;
     const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int g = rt.g;
-    const uint32_t T = p.tb.T[g];
+    const KeepThreshold T = keep_threshold(p.tb.T[g]);
     const lora_bf16* Ag = p.A + (int64_t)g * p.r * p.K;
 
     const lora_bf16* xrow[2];
@@ -42,14 +42,21 @@ __global__ void __launch_bounds__(DOWN_WAVES * 64) down_kernel(DownArgs p) {
     constexpr int DEPTH = CB == 1 ? 4 : 2;
     struct ChunkRegs { u32x4 x[2], a[CB]; };
     ChunkRegs ring[DEPTH];
-    auto load = [&](ChunkRegs& c, int kc) {
+    // Every workgroup starts its sweep over K at a different column (a function of its row-tile index
+    // within the segment, so that single- and multi-adapter calls sum in the same order): workgroups
+    // sweeping in lockstep would all hit the same few L2 channels, the row pitch being a multiple of
+    // the channel interleave.
+    const int rot = (int)(((unsigned)(rt.local_row0 / DOWN_ROWS) * 5u) % (unsigned)max(nchunks / DOWN_WAVES, 1)) * DOWN_WAVES;
+    auto load = [&](ChunkRegs& c, int kc0) {
+        const int kc = (kc0 + rot) % nchunks;
         const int col = kc * 32 + 8 * (l >> 4);
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) c.x[rb] = *(const u32x4*)(xrow[rb] + col);
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) c.a[cb] = *(const u32x4*)(Ag + (int64_t)(cb * 16 + (l & 15)) * p.K + col);
     };
-    auto consume = [&](const ChunkRegs& c, int kc) {
+    auto consume = [&](const ChunkRegs& c, int kc0) {
+        const int kc = (kc0 + rot) % nchunks;
         const uint32_t col = (uint32_t)(kc * 32 + 8 * (l >> 4));
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {

@@ -49,20 +49,10 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     const int cols_valid = min(kStreamChunk, p.C - c0);       // multiple of 64
     const int t = threadIdx.x, l = t & 63, w = t >> 6;
     const int g = rt.g;
-    const uint32_t T = p.tb.T[g], hk0 = p.tb.k0[g], hk1 = p.tb.k1[g];
+    const KeepThreshold T = keep_threshold(p.tb.T[g]);
+    const uint32_t hk0 = p.tb.k0[g], hk1 = p.tb.k1[g];
     // either output may be switched off (null pointer): the unfused baseline runs them as separate passes
     const bool do_red = p.part_out != nullptr, do_ds = !IS_DA && p.part_ds != nullptr;
-
-    if (!IS_DA) {
-        // B chunk [cols_valid, r] of adapter g -> LDS once (rows past the end are zero)
-        const lora_bf16* Bg = p.Bmat + ((int64_t)g * p.C + c0) * R;
-        for (int idx = t; idx < kStreamChunk * RCH; idx += ST_THREADS) {
-            const int row = idx / RCH, ch = idx - row * RCH;
-            u32x4 v = u32x4{0u, 0u, 0u, 0u};
-            if (row < cols_valid) v = *(const u32x4*)(Bg + (int64_t)row * R + ch * 8);
-            *(u32x4*)(lds_b + tile_off(row, ch, RCH)) = v;
-        }
-    }
 
     f32x4 acc[4][CB];
 #pragma unroll
@@ -106,6 +96,18 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
         if (t < ST_STEP * RCH) {
             const int row = t / RCH, ch = t - row * RCH;
             *(u32x4*)(lds_small + tile_off(row, ch, RCH)) = rg.s;
+        }
+    };
+
+    auto stage_b_chunk = [&]() {
+        if (IS_DA) return;
+        // B chunk [cols_valid, r] of adapter g -> LDS once (rows past the end are zero)
+        const lora_bf16* Bg = p.Bmat + ((int64_t)g * p.C + c0) * R;
+        for (int idx = t; idx < kStreamChunk * RCH; idx += ST_THREADS) {
+            const int row = idx / RCH, ch = idx - row * RCH;
+            u32x4 v = u32x4{0u, 0u, 0u, 0u};
+            if (row < cols_valid) v = *(const u32x4*)(Bg + (int64_t)row * R + ch * 8);
+            *(u32x4*)(lds_b + tile_off(row, ch, RCH)) = v;
         }
     };
 
@@ -174,6 +176,7 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
         StepRegs ra, rb2;
         load_step(ra, 0);
         if (nsteps > 1) load_step(rb2, 1);
+        stage_b_chunk();                               // after the first panel loads are in flight
         for (int step = 0; step < nsteps; step += 2) {
             store_step(ra, step);
             __syncthreads();
@@ -189,6 +192,7 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     } else {
         StepRegs ra;
         load_step(ra, 0);
+        stage_b_chunk();
         for (int step = 0; step < nsteps; ++step) {
             store_step(ra, step);
             __syncthreads();

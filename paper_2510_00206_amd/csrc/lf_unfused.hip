@@ -24,7 +24,7 @@ __global__ void __launch_bounds__(EW_THREADS) dropout_kernel(const lora_bf16* X,
     const int64_t row = idx / kc;
     const int col = (int)(idx - row * kc) * 8;
     u32x4 v = *(const u32x4*)(X + row * K + col);
-    v = mask8(v, row_key(k0, k1, (uint32_t)row), (uint32_t)col, T);
+    v = mask8(v, row_key(k0, k1, (uint32_t)row), (uint32_t)col, keep_threshold(T));
     u32x4 o;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -43,7 +43,7 @@ __global__ void __launch_bounds__(EW_THREADS) mask_scale_kernel(lora_bf16* V, in
     const int64_t row = idx / kc;
     const int col = (int)(idx - row * kc) * 8;
     u32x4 v = *(const u32x4*)(V + row * K + col);
-    v = mask8(v, row_key(k0, k1, (uint32_t)row), (uint32_t)col, T);
+    v = mask8(v, row_key(k0, k1, (uint32_t)row), (uint32_t)col, keep_threshold(T));
     u32x4 o;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
