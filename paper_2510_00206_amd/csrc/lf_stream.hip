@@ -42,7 +42,11 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     char* lds_b = lds_small + ST_STEP * R * 2;                // (3): B chunk [512][RCH chunks]
     char* lds_red = lds_b + (IS_DA ? 0 : kStreamChunk * R * 2);   // (3): [4][CB][64] f32x4
 
-    const int tile = blockIdx.x / p.chunks, chunk_id = blockIdx.x - tile * p.chunks;
+    // Consecutive workgroup ids go to different XCDs (private L2s).  The column chunk is skewed by the
+    // row tile so that one XCD does not end up reading a single column window of every row (which
+    // would crowd a few of its L2 channels, the row pitch being a multiple of the channel interleave).
+    const int tile = blockIdx.x / p.chunks;
+    const int chunk_id = (int)((blockIdx.x - tile * p.chunks + tile) % p.chunks);
     RowTile rt;
     if (!find_row_tile(p.tb, kRowTile, tile, rt)) return;
     const int c0 = chunk_id * kStreamChunk;
