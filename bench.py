@@ -38,6 +38,49 @@ def read_traffic(workload: str):
     return None
 
 
+def sweep(torch, binding, workloads, dev, args):
+    """The axes of the paper's Figure 3 / Figure 17 on this GPU: n = k = 4096, tokens swept, r in {16, 32};
+    forward and backward times of the fused LoRA linear, the unfused baseline and the frozen linear."""
+    def timed(fn, iters):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / iters * 1e6
+
+    for r in (16, 32):
+        for M in (1024, 2048, 4096, 8192, 16384):
+            L = workloads.custom_layer(M, 4096, 4096, r, 2.0, 0.1, cfg=6, name=f"sweep_m{M}_r{r}")
+            X, W, A, B, dY = (t.to(dev) for t in workloads.make_inputs(L))
+            A1, B1 = A[0].contiguous(), B[0].contiguous()
+            Y = torch.empty((M, 4096), dtype=torch.bfloat16, device=dev)
+            dX = torch.empty((M, 4096), dtype=torch.bfloat16, device=dev)
+            S = torch.empty((M, r), dtype=torch.bfloat16, device=dev)
+            dA = torch.empty((r, 4096), dtype=torch.float32, device=dev)
+            dB = torch.empty((4096, r), dtype=torch.float32, device=dev)
+            ws = binding.alloc_workspace(M, 4096, 4096, r, 1, dev)
+            uws = binding.unfused_workspace(M, 4096, 4096, r, dev)
+            it = max(10, min(args.steps, 200))
+            rec = {"sweep": "tokens x rank, K=N=4096", "tokens": M, "r": r,
+                   "fused_fwd_us": timed(lambda: binding.lora_fwd(X, W, A1, B1, L.s, L.p, L.seeds[0], Y=Y, S=S), it),
+                   "fused_bwd_us": timed(lambda: binding.lora_bwd(X, W, A1, B1, S, dY, L.s, L.p, L.seeds[0], dA=dA, dB=dB,
+                                                                  workspace=ws, dX=dX), it),
+                   "unfused_fwd_us": timed(lambda: binding.lora_unfused_fwd(X, W, A1, B1, L.s, L.p, L.seeds[0], uws, Y=Y), it),
+                   "unfused_bwd_us": timed(lambda: binding.lora_unfused_bwd(W, A1, B1, dY, L.s, L.p, L.seeds[0], uws,
+                                                                            dX=dX, dA=dA, dB=dB), it),
+                   "frozen_fwd_us": timed(lambda: binding.frozen_fwd(X, W, Y=Y), it),
+                   "frozen_bwd_us": timed(lambda: binding.frozen_bwd(dY, W, dX=dX), it)}
+            rec = {k: (round(v, 1) if isinstance(v, float) else v) for k, v in rec.items()}
+            rec["fused_over_frozen_fwd"] = round(rec["fused_fwd_us"] / rec["frozen_fwd_us"], 3)
+            rec["fused_over_frozen_bwd"] = round(rec["fused_bwd_us"] / rec["frozen_bwd_us"], 3)
+            rec["unfused_over_fused_fwd"] = round(rec["unfused_fwd_us"] / rec["fused_fwd_us"], 3)
+            rec["unfused_over_fused_bwd"] = round(rec["unfused_bwd_us"] / rec["fused_bwd_us"], 3)
+            print(json.dumps(rec), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -47,6 +90,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unfused", action="store_true",
                     help="time the unfused multi-kernel baseline instead of the fused path (comparison runs)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="token-count x rank sweep at K=N=4096: fused LoRA, unfused baseline and frozen linear (one JSON line each)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 1 GiB device copy 10 times (reference reading for HBM byte counters)")
     args = ap.parse_args()
@@ -69,6 +114,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "launches": 10}))
+        return
+    if args.sweep:
+        sweep(torch, binding, workloads, dev, args)
         return
     layers = workloads.CONFIGS[args.workload]
 

@@ -143,6 +143,13 @@ lora_status lora_unfused_bwd(const lora_bf16* W, const lora_bf16* A, const lora_
                              lora_bf16* dX, float* dA, float* dB, void* workspace, size_t workspace_bytes,
                              lora_stream stream);
 
+/* The frozen linear layer alone, with the same GEMM kernels (no adapter): Y = X W and dX = dY W^T.
+ * The reference line of the paper's Figure 3 (LoRA linear vs frozen linear).  M > 0. */
+lora_status lora_frozen_fwd(const lora_bf16* X, const lora_bf16* W, int64_t M, int64_t K, int64_t N, lora_bf16* Y,
+                            lora_stream stream);
+lora_status lora_frozen_bwd(const lora_bf16* dY, const lora_bf16* W, int64_t M, int64_t K, int64_t N, lora_bf16* dX,
+                            lora_stream stream);
+
 const char* lora_status_string(lora_status st);
 int lora_version(void);
 

@@ -49,6 +49,10 @@ def load_library() -> C.CDLL:
     lib.lora_unfused_workspace_bytes.restype = SZ
     lib.lora_unfused_fwd.argtypes = [P, P, P, P, I64, I64, I64, I32, F, F, U64, P, P, SZ, P]
     lib.lora_unfused_bwd.argtypes = [P, P, P, P, I64, I64, I64, I32, F, F, U64, P, P, P, P, SZ, P]
+    lib.lora_frozen_fwd.argtypes = [P, P, I64, I64, I64, P, P]
+    lib.lora_frozen_bwd.argtypes = [P, P, I64, I64, I64, P, P]
+    lib.lora_frozen_fwd.restype = C.c_int
+    lib.lora_frozen_bwd.restype = C.c_int
     lib.lora_unfused_fwd.restype = C.c_int
     lib.lora_unfused_bwd.restype = C.c_int
     lib.lora_profile_end.argtypes = [C.POINTER(F), C.POINTER(I32)]
@@ -200,3 +204,21 @@ def lora_unfused_bwd(W, A, B, dY, s, p, seed, workspace, dX=None, dA=None, dB=No
     _check(load_library().lora_unfused_bwd(_ptr(W), _ptr(A), _ptr(B), _ptr(dY), M, K, N, r, s, p, seed,
                                            _ptr(dX), _ptr(dA), _ptr(dB), _ptr(workspace), workspace.numel(), _stream()))
     return dX, dA, dB
+
+
+def frozen_fwd(X, W, Y=None):
+    """Y = X W^T (frozen linear alone, same GEMM kernel)."""
+    M, K = X.shape
+    N = W.shape[0]
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device) if Y is None else Y
+    _check(load_library().lora_frozen_fwd(_ptr(X), _ptr(W), M, K, N, _ptr(Y), _stream()))
+    return Y
+
+
+def frozen_bwd(dY, W, dX=None):
+    """dX = dY W (frozen linear alone; the frozen weight gets no gradient)."""
+    M, N = dY.shape
+    K = W.shape[1]
+    dX = torch.empty((M, K), dtype=torch.bfloat16, device=dY.device) if dX is None else dX
+    _check(load_library().lora_frozen_bwd(_ptr(dY), _ptr(W), M, K, N, _ptr(dX), _stream()))
+    return dX

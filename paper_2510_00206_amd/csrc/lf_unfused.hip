@@ -207,4 +207,22 @@ lora_status lora_unfused_bwd(const lora_bf16* W, const lora_bf16* A, const lora_
     return LORA_OK;
 }
 
+lora_status lora_frozen_fwd(const lora_bf16* X, const lora_bf16* W, int64_t M, int64_t K, int64_t N, lora_bf16* Y,
+                            lora_stream stream) {
+    if (!X || !W || !Y) return LORA_ERR_NULL;
+    if (!supported(M, K, N, 16)) return LORA_ERR_UNSUPPORTED;
+    const AdapterTable plain = make_table(M, 1.f, 0.f, 0, true);
+    LF_TRY(launch_fwd_gemm(FwdGemmArgs{X, W, nullptr, nullptr, Y, (int)M, (int)K, (int)N, 0, 0, 0, plain}, (hipStream_t)stream));
+    return LORA_OK;
+}
+
+lora_status lora_frozen_bwd(const lora_bf16* dY, const lora_bf16* W, int64_t M, int64_t K, int64_t N, lora_bf16* dX,
+                            lora_stream stream) {
+    if (!dY || !W || !dX) return LORA_ERR_NULL;
+    if (!supported(M, K, N, 16)) return LORA_ERR_UNSUPPORTED;
+    const AdapterTable plain = make_table(M, 1.f, 0.f, 0, true);
+    LF_TRY(launch_bwd_dx(DxGemmArgs{dY, W, nullptr, nullptr, dX, (int)M, (int)K, (int)N, 0, 0, 0, plain}, (hipStream_t)stream));
+    return LORA_OK;
+}
+
 }  // extern "C"

@@ -168,3 +168,15 @@ def test_unfused_baseline_parity(shape):
     torch.cuda.synchronize()
     ref = run_oracle(L, X, W, A, B, dY)
     compare(dict(Y=Y, dX=dX, dA=dA[None], dB=dB[None]), ref, label=f"unfused {shape}")
+
+
+def test_frozen_linear_reference_line():
+    """The frozen linear alone (the reference line of the LoRA-overhead sweep) is the plain products."""
+    L = workloads.custom_layer(300, 320, 448, 16, cfg=5)
+    X, W, A, B, dY = workloads.make_inputs(L)
+    print("frozen linear", flush=True)
+    Y = binding.frozen_fwd(X.cuda(), W.cuda())
+    dX = binding.frozen_bwd(dY.cuda(), W.cuda())
+    torch.cuda.synchronize()
+    assert rel_err(Y, f64(X) @ f64(W).T) <= TOL / 4
+    assert rel_err(dX, f64(dY) @ f64(W)) <= TOL / 4
