@@ -32,9 +32,10 @@
  * - Ownership: the caller owns every buffer.  No entry point allocates or frees device
  *   memory, synchronises the device, or touches a stream other than `stream`; work is only
  *   enqueued.  Inputs are never modified.
- * - Supported sizes: M >= 0 (M == 0 is a no-op), K and N positive multiples of 64,
- *   r in {16, 32, 64}, 1 <= G <= 64, M < 2^31.
+ * - Supported sizes: M >= 0 (M == 0 is a no-op), K and N positive multiples of 64 and at most
+ *   2^22, r in {16, 32, 64}, 1 <= G <= 64, M < 2^31.
  * - Errors: every call returns a lora_status and enqueues nothing unless it returns LORA_OK.
+ *   With M == 0 the token-sized arrays (X, Y, S_saved, dY, dX) are empty and may be NULL.
  */
 #ifndef LORAFUSION_H
 #define LORAFUSION_H
@@ -54,7 +55,7 @@ typedef enum {
     LORA_ERR_PARAM = 4,       /* p outside [0,1), or p/s not finite */
     LORA_ERR_SEGMENTS = 5,    /* offsets do not rise from 0 to M */
     LORA_ERR_WORKSPACE = 6,   /* workspace smaller than lora_bwd_workspace_bytes() */
-    LORA_ERR_UNSUPPORTED = 7, /* K or N not a multiple of 64, r not in {16,32,64}, G > 64 */
+    LORA_ERR_UNSUPPORTED = 7, /* K or N not a multiple of 64 or above 2^22, r not in {16,32,64}, G > 64 */
     LORA_ERR_HIP = 8          /* a kernel launch failed */
 } lora_status;
 

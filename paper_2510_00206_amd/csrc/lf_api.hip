@@ -20,6 +20,7 @@ lora_status check_shape(int64_t M, int64_t K, int64_t N, int32_t r, int32_t G) {
     if (M < 0 || K <= 0 || N <= 0 || M >= (1ll << 31) || K >= (1ll << 31) || N >= (1ll << 31)) return LORA_ERR_SHAPE;
     if (G < 1) return LORA_ERR_SHAPE;
     if ((K & 63) || (N & 63) || !(r == 16 || r == 32 || r == 64) || G > kMaxAdapters) return LORA_ERR_UNSUPPORTED;
+    if (K > (1 << 22) || N > (1 << 22)) return LORA_ERR_UNSUPPORTED;   // per-lane slab offsets are 32-bit
     return LORA_OK;
 }
 
@@ -131,7 +132,9 @@ lora_status multi_lora_fwd(const lora_bf16* X, const lora_bf16* W, const lora_bf
                            int64_t M, int64_t K, int64_t N, int32_t r, int32_t G,
                            const int64_t* seg_offsets, const float* s, const float* p, const uint64_t* seeds,
                            lora_bf16* Y, lora_bf16* S_saved, lora_stream stream) {
-    if (!X || !W || !A || !B || !Y || !S_saved || !seg_offsets || !s || !p || !seeds) return LORA_ERR_NULL;
+    // with M == 0 the token-sized arrays are empty and may be NULL
+    if (!W || !A || !B || !seg_offsets || !s || !p || !seeds) return LORA_ERR_NULL;
+    if (M != 0 && (!X || !Y || !S_saved)) return LORA_ERR_NULL;
     lora_status st = check_shape(M, K, N, r, G);
     if (st != LORA_OK) return st;
     if (misaligned(X) || misaligned(W) || misaligned(A) || misaligned(B) || misaligned(Y) || misaligned(S_saved))
@@ -156,8 +159,8 @@ lora_status multi_lora_bwd(const lora_bf16* X, const lora_bf16* W, const lora_bf
                            const int64_t* seg_offsets, const float* s, const float* p, const uint64_t* seeds,
                            lora_bf16* dX, float* dA, float* dB, int accumulate,
                            void* workspace, size_t workspace_bytes, lora_stream stream) {
-    if (!X || !W || !A || !B || !S_saved || !dY || !dA || !dB || !workspace || !seg_offsets || !s || !p || !seeds)
-        return LORA_ERR_NULL;
+    if (!W || !A || !B || !dA || !dB || !workspace || !seg_offsets || !s || !p || !seeds) return LORA_ERR_NULL;
+    if (M != 0 && (!X || !S_saved || !dY)) return LORA_ERR_NULL;
     lora_status st = check_shape(M, K, N, r, G);
     if (st != LORA_OK) return st;
     if (misaligned(X) || misaligned(W) || misaligned(A) || misaligned(B) || misaligned(S_saved) ||

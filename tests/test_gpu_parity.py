@@ -180,3 +180,37 @@ def test_frozen_linear_reference_line():
     torch.cuda.synchronize()
     assert rel_err(Y, f64(X) @ f64(W).T) <= TOL / 4
     assert rel_err(dX, f64(dY) @ f64(W)) <= TOL / 4
+
+
+def test_empty_batch_and_many_adapters():
+    """M = 0 is a no-op forward and a zero-fill backward; 64 adapters (the table's capacity) with
+    short uneven segments, several of them empty."""
+    K, N, r = 128, 192, 16
+    dev = "cuda"
+    W = torch.randn(N, K, device=dev).to(torch.bfloat16)
+    A = torch.randn(1, r, K, device=dev).to(torch.bfloat16)
+    B = torch.randn(1, N, r, device=dev).to(torch.bfloat16)
+    X0 = torch.empty((0, K), dtype=torch.bfloat16, device=dev)
+    dY0 = torch.empty((0, N), dtype=torch.bfloat16, device=dev)
+    print("M = 0", flush=True)
+    Y, S = binding.multi_lora_fwd(X0, W, A, B, [0, 0], [1.0], [0.1], [1])
+    assert Y.shape == (0, N)
+    dA = torch.full((1, r, K), 7.0, device=dev)
+    dB = torch.full((1, N, r), 7.0, device=dev)
+    binding.multi_lora_bwd(X0, W, A, B, S, dY0, [0, 0], [1.0], [0.1], [1], dA=dA, dB=dB)
+    torch.cuda.synchronize()
+    assert not dA.any() and not dB.any()
+
+    G = 64
+    rng = np.random.default_rng(11)
+    lens = [int(v) for v in rng.integers(0, 40, size=G)]
+    lens[3] = lens[17] = 0
+    L = workloads.custom_layer(sum(lens), 192, 128, 16, 2.0, 0.1, seg_lens=lens, cfg=1)
+    print(f"G = 64, M = {L.M}", flush=True)
+    inp = workloads.make_inputs(L)
+    gpu = run_gpu(L, *inp)
+    compare(gpu, run_oracle(L, *inp), label="64 adapters")
+    with pytest.raises(binding.LoraError) as e:
+        binding.multi_lora_fwd(gpu["Y"].new_empty((L.M, 192)), W[:, :192].contiguous(), inp[2].cuda().repeat(2, 1, 1)[:65],
+                               inp[3].cuda().repeat(2, 1, 1)[:65], list(range(0, 65)) + [L.M], [1.0] * 65, [0.1] * 65, [1] * 65)
+    assert e.value.status in (5, 7)
