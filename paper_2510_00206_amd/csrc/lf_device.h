@@ -51,6 +51,32 @@ __device__ __forceinline__ bool find_row_tile(const AdapterTable& tb, int gran, 
     return false;
 }
 
+__device__ __forceinline__ int segment_of_row(const AdapterTable& tb, int row) {
+    int g = 0;
+    while (g + 1 < tb.G && row >= tb.row0[g + 1]) ++g;
+    return g;
+}
+
+// Packed tiling for the GEMMs: when every segment boundary is a multiple of 64 rows, the packed
+// batch is cut into uniform 256-row tiles and a tile may hold up to four adapters, one per 64-row
+// group; only such mixed tiles take the slower per-group LoRA path.
+struct GroupMap { int g[4]; bool mixed; };
+
+__device__ __forceinline__ void find_uniform_tile(const AdapterTable& tb, int M, int gran, int tile, RowTile& rt,
+                                                  GroupMap& gm) {
+    rt.row_start = tile * gran;
+    rt.rows = min(gran, M - rt.row_start);
+    gm.mixed = false;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int row = rt.row_start + 64 * q;
+        gm.g[q] = (q == 0 || row < M) ? segment_of_row(tb, row) : gm.g[q - 1];
+        if (q > 0 && gm.g[q] != gm.g[0]) gm.mixed = true;
+    }
+    rt.g = gm.g[0];
+    rt.local_row0 = rt.row_start - tb.row0[rt.g];
+}
+
 // ---- dropout hash (unsigned 32-bit arithmetic) ------------------------------------------------
 constexpr uint32_t kGold = 0x9E3779B9u, kM1 = 0x6A09E667u, kM2 = 0xBB67AE85u, kC5 = 0x3C6EF373u,
                    kC7 = 0xA54FF53Bu;

@@ -301,13 +301,74 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[4][4]) {
             for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
 }
 
+// gm.g[q] for a run-time q, as a scalar (wave-uniform) value
+__device__ __forceinline__ int group_adapter(const GroupMap& gm, int q) {
+    const int g = q == 0 ? gm.g[0] : q == 1 ? gm.g[1] : q == 2 ? gm.g[2] : gm.g[3];
+    return __builtin_amdgcn_readfirstlane(g);
+}
+
+// LoRA step of a tile that holds several adapters (FusedMultiLoRA with tiles cut uniformly over the
+// packed batch).  The runs of 64-row groups that share an adapter become column blocks of one wide
+// contraction: token operand row i carries S'[i, :] in the block of its own run and zeros elsewhere,
+// out operand column n carries B_g[n, :] of run j's adapter in block j, so the ordinary LoRA sub-steps
+// add exactly S'_i . B_g(i) (the other blocks contribute exact zeros).  runs * r <= 128 contraction
+// columns fit: chunks 0..7 of each row go to stage `lo`, chunks 8..15 to the other stage.  Written
+// with ordinary stores (zeros cannot come from a global->LDS copy); returns the number of sub-steps.
+__device__ __forceinline__ int build_mixed_lora_slabs(char* smem, int lo, const lora_bf16* S_tile,
+                                                      const lora_bf16* B, int N, int n0, int r, int rows_valid,
+                                                      int cols_valid, const GroupMap& gm) {
+    const int nq = (rows_valid + 63) >> 6;
+    int run_of_q[4], g_of_run[4];
+    int nruns = 1;
+    run_of_q[0] = 0;
+    g_of_run[0] = g_of_run[1] = g_of_run[2] = g_of_run[3] = gm.g[0];
+#pragma unroll
+    for (int q = 1; q < 4; ++q) {
+        if (q < nq && gm.g[q] != gm.g[q - 1]) {
+            if (nruns == 1) g_of_run[1] = gm.g[q];
+            else if (nruns == 2) g_of_run[2] = gm.g[q];
+            else g_of_run[3] = gm.g[q];
+            ++nruns;
+        }
+        run_of_q[q] = nruns - 1;
+    }
+    const int rc = r >> 3;                               // 16-byte chunks per adapter block: 2, 4 or 8
+    const int rc_shift = rc == 2 ? 1 : rc == 4 ? 2 : 3;
+    __syncthreads();                                     // every wave is done with both stages
+#pragma unroll 1
+    for (int idx = threadIdx.x; idx < BM * 16; idx += NTHREADS) {
+        const int row = idx >> 4, cc = idx & 15;
+        const int j = cc >> rc_shift, sub = cc & (rc - 1);
+        const int q = row >> 6;
+        const int rq = q == 0 ? run_of_q[0] : q == 1 ? run_of_q[1] : q == 2 ? run_of_q[2] : run_of_q[3];
+        const int gj = j == 0 ? g_of_run[0] : j == 1 ? g_of_run[1] : j == 2 ? g_of_run[2] : g_of_run[3];
+        u32x4 tv = {0u, 0u, 0u, 0u}, bv = {0u, 0u, 0u, 0u};
+        if (j < nruns) {
+            if (rq == j) tv = *(const u32x4*)(S_tile + (int64_t)min(row, rows_valid - 1) * r + sub * 8);
+            bv = *(const u32x4*)(B + ((int64_t)gj * N + n0 + min(row, cols_valid - 1)) * r + sub * 8);
+        }
+        char* dst = smem + ((cc & 8) ? STAGE_BYTES - lo : lo) + row_slab_off(row, cc & 7);
+        *(u32x4*)dst = tv;
+        *(u32x4*)(dst + TILE_BYTES) = bv;
+    }
+    __syncthreads();
+    return nruns * (r >> 4);
+}
+
 // ---- operation (2): Y = X W + S' B ---------------------------------------------------------------
 __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int tm, tn;
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
     RowTile rt;
-    if (!find_row_tile(p.tb, BM, tm, rt)) return;
+    GroupMap gm;
+    if (p.uniform_tiles) {
+        find_uniform_tile(p.tb, p.M, BM, tm, rt, gm);
+    } else {
+        if (!find_row_tile(p.tb, BM, tm, rt)) return;
+        gm.g[0] = gm.g[1] = gm.g[2] = gm.g[3] = rt.g;
+        gm.mixed = false;
+    }
     const int n0 = tn * BN;
     const int cols_valid = min(BN, p.N - n0);
     const int w = threadIdx.x >> 6, wm = w & 1, wn = w >> 1;
@@ -353,18 +414,27 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
         // out operand B [N, r]
         const int cur = ((nk - 1) & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
         const NextSlabs nx{(const char*)Ssrc, (const char*)Bsrc, ss, sb,
-                           lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, has_lora};
+                           lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, has_lora && !gm.mixed};
         slab_step<false>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
                          smem + nxt + out_org, fl, nx);
     }
     if (has_lora) {
         const int lo = (nk & 1) * STAGE_BYTES;         // the stage that holds the LoRA slab
+        int nkk = p.r / 16;
+        if (gm.mixed) {
+            // a tile with several adapters: both stages are rebuilt as one wide LoRA slab pair (below)
+            nkk = build_mixed_lora_slabs(smem, lo, Ssrc, p.B, p.N, n0, p.r, rt.rows, cols_valid, gm);
+            read_frags<false>(f0, smem + lo + tok_org, smem + lo + out_org, fl, fl.row_off[0], 0);
+        }
         mma_frags<0, 4>(acc, f0);
         const int l = threadIdx.x & 63;
 #pragma unroll 1
-        for (int kk = 1; kk < p.r / 16; ++kk) {
+        for (int kk = 1; kk < nkk; ++kk) {
+            // sub-steps 4..7 (mixed tiles only) live in the other stage
+            const int st = (kk & 4) ? STAGE_BYTES - lo : lo;
             Frags f;
-            read_frags<false>(f, smem + lo + tok_org, smem + lo + out_org, fl, row_slab_off(l & 31, 2 * kk + (l >> 5)), 0);
+            read_frags<false>(f, smem + st + tok_org, smem + st + out_org, fl,
+                              row_slab_off(l & 31, 2 * (kk & 3) + (l >> 5)), 0);
             mma_frags<0, 4>(acc, f);
         }
     }
@@ -377,7 +447,14 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     int tm, tn;
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
     RowTile rt;
-    if (!find_row_tile(p.tb, BM, tm, rt)) return;
+    GroupMap gm;
+    if (p.uniform_tiles) {
+        find_uniform_tile(p.tb, p.M, BM, tm, rt, gm);
+    } else {
+        if (!find_row_tile(p.tb, BM, tm, rt)) return;
+        gm.g[0] = gm.g[1] = gm.g[2] = gm.g[3] = rt.g;
+        gm.mixed = false;
+    }
     const int j0 = tn * BN;                          // output columns are input features
     const int cols_valid = min(BN, p.K - j0);
     const int w = threadIdx.x >> 6, wm = w & 1, wn = w >> 1;
@@ -396,59 +473,76 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     // base-gradient contraction continues on top of them.
     // p.r == 0 (no LoRA term) and p.N == 0 (LoRA term only) serve the unfused baseline's plain GEMMs.
     const int nk = p.N / BK;
+    const SlabLanes ss = row_slab_lanes(p.r > 0 ? p.r : 16, rt.rows, p.r > 0 ? p.r >> 3 : 2);
+    const SlabLanes sa = col_slab_lanes(p.K, p.r > 0 ? p.r : 16, cols_valid);
     if (p.r > 0) {
-        const SlabLanes ss = row_slab_lanes(p.r, rt.rows, p.r >> 3), sa = col_slab_lanes(p.K, p.r, cols_valid);
         load_slab(lds0 + STAGE_BYTES, p.dS + (int64_t)rt.row_start * p.r, ss);
-        load_slab(lds0 + STAGE_BYTES + TILE_BYTES, p.A + (int64_t)rt.g * p.r * p.K + j0, sa);
+        load_slab(lds0 + STAGE_BYTES + TILE_BYTES, p.A + (int64_t)gm.g[0] * p.r * p.K + j0, sa);
     }
     if (nk > 0) {
-        load_slab(lds0, dYt, sd);
+        load_slab(lds0, dYt + 0, sd);
         load_slab(lds0 + TILE_BYTES, Wt, sw);
     }
     wait_slab_loads();
     __syncthreads();
     if (p.r > 0) {
-        // one 32x32 block at a time: t = dS A^T on a fresh accumulator, masked and scaled, becomes the
-        // block's starting value.  The hash of a block overlaps the MFMAs of the next one.
-        const uint32_t T = p.tb.T[rt.g];
-        const float q = p.tb.q[rt.g];
-        const uint32_t k0 = p.tb.k0[rt.g], k1 = p.tb.k1[rt.g];
+        // One run of 64-row groups per adapter present in the tile (a single run unless the tile is
+        // mixed).  Within a run, one 32x32 block at a time: t = dS A^T on a fresh accumulator, masked and
+        // scaled, becomes the block's starting value; the hash of a block overlaps the next block's MFMAs.
         const int l = threadIdx.x & 63;
         const int nkk = p.r / 16;
         const char* lds_tok = smem + STAGE_BYTES + tok_org;
         const char* lds_out = smem + STAGE_BYTES + out_org;
         const uint32_t cp0 = (uint32_t)(j0 + wn * 128 + 4 * (l >> 5)) >> 1;     // this lane's first column pair
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi) {
-            const int row = wm * 128 + mi * 32 + (l & 31);
-            const RowKey rk = row_key(k0, k1, (uint32_t)(rt.local_row0 + row));
-            const uint32_t x0 = rk.a + cp0 * kGold;
-#pragma unroll
-            for (int ni = 0; ni < 4; ++ni) {
-                f32x16 t;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) t[i] = 0.f;
-#pragma unroll 1
-                for (int kk = 0; kk < nkk; ++kk) {
-                    const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni][0] + kk * 8192);
-                    const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni][1] + kk * 8192);
-                    const bf16x8 ft = __builtin_bit_cast(
-                        bf16x8, *(const u32x4*)(lds_tok + row_slab_off(l & 31, 2 * kk + (l >> 5)) + mi * 4096));
-                    t = LF_MFMA(join_tr(lo, hi), ft, t);
-                }
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    // columns ni*32 + 8*g4 + {0..3} past the lane's first column: pairs (ni*16 + 4*g4) + {0, 1}
-                    const uint32_t w0 = hash_word_at(rk, x0 + (uint32_t)(ni * 16 + 4 * g4) * kGold);
-                    const uint32_t w1 = hash_word_at(rk, x0 + (uint32_t)(ni * 16 + 4 * g4 + 1) * kGold);
-                    f32x16& a = acc[mi][ni];
-                    a[4 * g4 + 0] = (w0 & 0xFFFFu) >= T ? t[4 * g4 + 0] * q : 0.f;
-                    a[4 * g4 + 1] = (w0 >> 16) >= T ? t[4 * g4 + 1] * q : 0.f;
-                    a[4 * g4 + 2] = (w1 & 0xFFFFu) >= T ? t[4 * g4 + 2] * q : 0.f;
-                    a[4 * g4 + 3] = (w1 >> 16) >= T ? t[4 * g4 + 3] * q : 0.f;
-                }
-                asm volatile("" : "+a"(acc[mi][ni]));    // the block is final here: nothing sinks past
+        const int nq = (rt.rows + 63) >> 6;
+        for (int q = 0; q < nq;) {
+            const int g = group_adapter(gm, q);
+            int qe = q + 1;
+            while (qe < nq && group_adapter(gm, qe) == g) ++qe;
+            if (q > 0) {                               // next adapter of a mixed tile: bring its A slab
+                __syncthreads();
+                load_slab(lds0 + STAGE_BYTES + TILE_BYTES, p.A + (int64_t)g * p.r * p.K + j0, sa);
+                wait_slab_loads();
+                __syncthreads();
             }
+            const uint32_t T = p.tb.T[g];
+            const float qs = p.tb.q[g];
+            const uint32_t k0 = p.tb.k0[g], k1 = p.tb.k1[g];
+            const int lrow0 = rt.row_start - p.tb.row0[g];        // tile row -> row inside the adapter's segment
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi) {
+                const int row = wm * 128 + mi * 32 + (l & 31);
+                if (wm * 128 + mi * 32 < 64 * q || wm * 128 + mi * 32 >= 64 * qe) continue;
+                const RowKey rk = row_key(k0, k1, (uint32_t)(lrow0 + row));
+                const uint32_t x0 = rk.a + cp0 * kGold;
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni) {
+                    f32x16 t;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) t[i] = 0.f;
+#pragma unroll 1
+                    for (int kk = 0; kk < nkk; ++kk) {
+                        const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni][0] + kk * 8192);
+                        const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni][1] + kk * 8192);
+                        const bf16x8 ft = __builtin_bit_cast(
+                            bf16x8, *(const u32x4*)(lds_tok + row_slab_off(l & 31, 2 * kk + (l >> 5)) + mi * 4096));
+                        t = LF_MFMA(join_tr(lo, hi), ft, t);
+                    }
+#pragma unroll
+                    for (int g4 = 0; g4 < 4; ++g4) {
+                        // columns ni*32 + 8*g4 + {0..3} past the lane's first column: pairs (ni*16 + 4*g4) + {0, 1}
+                        const uint32_t w0 = hash_word_at(rk, x0 + (uint32_t)(ni * 16 + 4 * g4) * kGold);
+                        const uint32_t w1 = hash_word_at(rk, x0 + (uint32_t)(ni * 16 + 4 * g4 + 1) * kGold);
+                        f32x16& a = acc[mi][ni];
+                        a[4 * g4 + 0] = (w0 & 0xFFFFu) >= T ? t[4 * g4 + 0] * qs : 0.f;
+                        a[4 * g4 + 1] = (w0 >> 16) >= T ? t[4 * g4 + 1] * qs : 0.f;
+                        a[4 * g4 + 2] = (w1 & 0xFFFFu) >= T ? t[4 * g4 + 2] * qs : 0.f;
+                        a[4 * g4 + 3] = (w1 >> 16) >= T ? t[4 * g4 + 3] * qs : 0.f;
+                    }
+                    asm volatile("" : "+a"(acc[mi][ni]));    // the block is final here: nothing sinks past
+                }
+            }
+            q = qe;
         }
     }
     __syncthreads();                                  // every wave is done with the LoRA slab in stage 1
@@ -466,6 +560,30 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
 }
 
 // ---- host launchers -------------------------------------------------------------------------------
+// Uniform 256-row tiles over the packed batch are possible when every segment boundary is a multiple
+// of 64 rows (a tile then holds at most four adapters, one per 64-row group).
+static bool boundaries_on_64(const AdapterTable& tb) {
+    for (int g = 0; g <= tb.G; ++g)
+        if (tb.row0[g] & 63) return false;
+    return true;
+}
+
+// Largest number of adapter runs (maximal sequences of 64-row groups with one adapter) in any uniform tile.
+static int max_runs_per_tile(const AdapterTable& tb, int M) {
+    int worst = 1;
+    for (int t0 = 0; t0 < M; t0 += BM) {
+        int runs = 0, prev = -1;
+        for (int row = t0; row < t0 + BM && row < M; row += 64) {
+            int g = 0;
+            while (g + 1 < tb.G && row >= tb.row0[g + 1]) ++g;
+            if (g != prev) ++runs;
+            prev = g;
+        }
+        if (runs > worst) worst = runs;
+    }
+    return worst;
+}
+
 static int count_row_tiles(const AdapterTable& tb, int gran) {
     int n = 0;
     for (int g = 0; g < tb.G; ++g) n += (tb.row0[g + 1] - tb.row0[g] + gran - 1) / gran;
@@ -473,7 +591,9 @@ static int count_row_tiles(const AdapterTable& tb, int gran) {
 }
 
 hipError_t launch_fwd_gemm(FwdGemmArgs a, hipStream_t st) {
-    a.tiles_m = count_row_tiles(a.tb, BM);
+    // a mixed tile's LoRA step holds runs * r contraction columns in the two LDS stages: at most 128
+    a.uniform_tiles = a.tb.G > 1 && boundaries_on_64(a.tb) && max_runs_per_tile(a.tb, a.M) * a.r <= 128;
+    a.tiles_m = a.uniform_tiles ? (a.M + BM - 1) / BM : count_row_tiles(a.tb, BM);
     a.tiles_n = (a.N + BN - 1) / BN;
     if (a.tiles_m == 0) return hipSuccess;
     static bool attr_set = false;
@@ -488,7 +608,8 @@ hipError_t launch_fwd_gemm(FwdGemmArgs a, hipStream_t st) {
 }
 
 hipError_t launch_bwd_dx(DxGemmArgs a, hipStream_t st) {
-    a.tiles_m = count_row_tiles(a.tb, BM);
+    a.uniform_tiles = a.tb.G > 1 && boundaries_on_64(a.tb);
+    a.tiles_m = a.uniform_tiles ? (a.M + BM - 1) / BM : count_row_tiles(a.tb, BM);
     a.tiles_n = (a.K + BN - 1) / BN;
     if (a.tiles_m == 0) return hipSuccess;
     static bool attr_set = false;

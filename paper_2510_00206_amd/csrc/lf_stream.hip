@@ -263,12 +263,6 @@ hipError_t launch_stream_da(StreamArgs a, hipStream_t st) {
 }
 
 // ---- finalize: fixed-order sums of the partials ---------------------------------------------------
-__device__ __forceinline__ int segment_of_row(const AdapterTable& tb, int row) {
-    int g = 0;
-    while (g + 1 < tb.G && row >= tb.row0[g + 1]) ++g;
-    return g;
-}
-
 // job 1: dS[i, c..c+3] = bf16(s_g * sum_chunks part_ds);  job 2: dB[g, n, c..c+3] (+)= sum over tiles of g
 __global__ void __launch_bounds__(256) finalize_ds_db_kernel(FinalizeArgs p, int blocks_ds) {
     const int r4 = p.r >> 2;

@@ -78,7 +78,10 @@ MULTI = [  # M, K, N, r, segment lengths
     (768, 256, 320, 16, (256, 128, 384)),
     (640, 192, 256, 16, (64, 0, 320, 256)),            # an empty segment
     (601, 320, 192, 32, (100, 37, 300, 164)),          # boundaries off the 64 grid
-    (1024, 512, 1088, 64, (128, 640, 256)),            # r = 64
+    (1024, 512, 1088, 64, (128, 640, 256)),            # r = 64, row tiles with two adapters
+    (832, 256, 320, 16, (64, 64, 64, 64, 192, 0, 64, 320)),   # four adapters inside one 256-row tile
+    (704, 192, 448, 32, (64, 64, 64, 64, 128, 192, 128)),     # r = 32 x 4 adapters: the widest mixed LoRA step
+    (576, 256, 256, 64, (64, 128, 64, 320)),           # r = 64 x 3 adapters in a tile: per-segment tiles instead
 ]
 
 
