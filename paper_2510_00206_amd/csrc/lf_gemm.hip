@@ -288,7 +288,9 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[4][4], lora_bf16*
         if (r & 1) v = u32x4{v.z, v.w, v.x, v.y};      // odd rows hold the two slots of a chunk swapped
         const int row = wm * 128 + r;
         if (col_ok && row < rows_valid)
-            *(u32x4*)(out + (int64_t)(row_start + row) * ld + col_start + wn * 128 + j * 8) = v;
+            // write-once output: a non-temporal store keeps it from displacing the operands (and the
+            // activations that the next kernels re-read) in the L2 and the memory-side cache
+            __builtin_nontemporal_store(v, (u32x4*)(out + (int64_t)(row_start + row) * ld + col_start + wn * 128 + j * 8));
     }
 }
 
@@ -299,6 +301,12 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[4][4]) {
         for (int ni = 0; ni < 4; ++ni)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+    // pin the 256 register writes here (callers place them between the issue of the first slab copies
+    // and the wait for them); otherwise they are sunk to the first use, after the wait
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) asm volatile("" : "+a"(acc[mi][ni]));
 }
 
 // gm.g[q] for a run-time q, as a scalar (wave-uniform) value
@@ -377,7 +385,6 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     const lora_bf16* Wt = p.W + (int64_t)n0 * p.K;
 
     f32x16 acc[4][4];
-    zero_acc(acc);
 
     const int nk = p.K / BK;
     const uint32_t lds0 = lds_addr_of(smem);
@@ -397,6 +404,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
         load_slab(lds0, Ssrc, ss);
         load_slab(lds0 + TILE_BYTES, Bsrc, sb);
     }
+    zero_acc(acc);                                     // while the first slabs are on their way
     wait_slab_loads();
     __syncthreads();
     Frags f0, f1;
@@ -460,7 +468,6 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     const int w = threadIdx.x >> 6, wm = w & 1, wn = w >> 1;
 
     f32x16 acc[4][4];
-    zero_acc(acc);
 
     const lora_bf16* dYt = p.dY + (int64_t)rt.row_start * p.N;
     const lora_bf16* Wt = p.W + j0;
@@ -483,6 +490,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
         load_slab(lds0, dYt + 0, sd);
         load_slab(lds0 + TILE_BYTES, Wt, sw);
     }
+    zero_acc(acc);                                     // while the first slabs are on their way
     wait_slab_loads();
     __syncthreads();
     if (p.r > 0) {
