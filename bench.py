@@ -84,10 +84,14 @@ def sweep(torch, binding, workloads, dev, args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2", help="c1..c5 (default c2, the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rotate", type=int, default=1,
+                    help="number of independent buffer sets (inputs, weights, outputs, workspace) used round-robin, "
+                         "one per step; with enough sets (> 256 MB in total) no step finds its tensors in the "
+                         "memory-side cache.  Default 1: back-to-back steps on the same buffers")
     ap.add_argument("--unfused", action="store_true",
                     help="time the unfused multi-kernel baseline instead of the fused path (comparison runs)")
     ap.add_argument("--sweep", action="store_true",
@@ -121,27 +125,38 @@ def main():
     layers = workloads.CONFIGS[args.workload]
 
     # inputs, outputs and workspaces resident in HBM before the timed region
-    state = []
-    for li, L in enumerate(layers):
-        X, W, A, B, dY = (t.to(dev) for t in workloads.make_inputs(L, layer_index=li))
-        st = dict(L=L, X=X, W=W, A=A, B=B, dY=dY,
-                  Y=torch.empty((L.M, L.N), dtype=torch.bfloat16, device=dev),
-                  S=torch.empty((L.M, L.r), dtype=torch.bfloat16, device=dev),
-                  dA=torch.empty((L.G, L.r, L.K), dtype=torch.float32, device=dev),
-                  dB=torch.empty((L.G, L.N, L.r), dtype=torch.float32, device=dev),
-                  ws=binding.alloc_workspace(L.M, L.K, L.N, L.r, L.G, dev),
-                  s=[L.s] * L.G, p=[L.p] * L.G)
-        state.append(st)
+    def make_state():
+        state = []
+        for li, L in enumerate(layers):
+            X, W, A, B, dY = (t.to(dev) for t in workloads.make_inputs(L, layer_index=li))
+            st = dict(L=L, X=X, W=W, A=A, B=B, dY=dY,
+                      Y=torch.empty((L.M, L.N), dtype=torch.bfloat16, device=dev),
+                      S=torch.empty((L.M, L.r), dtype=torch.bfloat16, device=dev),
+                      dX=torch.empty((L.M, L.K), dtype=torch.bfloat16, device=dev),
+                      dA=torch.empty((L.G, L.r, L.K), dtype=torch.float32, device=dev),
+                      dB=torch.empty((L.G, L.N, L.r), dtype=torch.float32, device=dev),
+                      ws=binding.alloc_workspace(L.M, L.K, L.N, L.r, L.G, dev),
+                      s=[L.s] * L.G, p=[L.p] * L.G)
+            state.append(st)
+        return state
+
+    sets = [make_state()]
+    for _ in range(1, max(1, args.rotate)):
+        # further sets: same values, separate memory
+        sets.append([{k: (v.clone() if isinstance(v, torch.Tensor) else v) for k, v in st.items()} for st in sets[0]])
+    state = sets[0]
+    step_no = [0]
 
     if args.unfused:
-        for st in state:
+        for st in (st for one in sets for st in one):
             assert st["L"].G == 1, "the unfused baseline is single-adapter"
             st["uws"] = binding.unfused_workspace(st["L"].M, st["L"].K, st["L"].N, st["L"].r, dev)
             st["A1"], st["B1"] = st["A"][0].contiguous(), st["B"][0].contiguous()
-            st["dX"] = torch.empty((st["L"].M, st["L"].K), dtype=torch.bfloat16, device=dev)
 
     def step():
-        for st in state:
+        cur = sets[step_no[0] % len(sets)]
+        step_no[0] += 1
+        for st in cur:
             L = st["L"]
             if args.unfused:
                 binding.lora_unfused_fwd(st["X"], st["W"], st["A1"], st["B1"], L.s, L.p, L.seeds[0], st["uws"], Y=st["Y"])
@@ -150,9 +165,9 @@ def main():
                 continue
             binding.multi_lora_fwd(st["X"], st["W"], st["A"], st["B"], L.seg_offsets, st["s"], st["p"], L.seeds,
                                    Y=st["Y"], S=st["S"])
-            st["dX"] = binding.multi_lora_bwd(st["X"], st["W"], st["A"], st["B"], st["S"], st["dY"], L.seg_offsets,
-                                              st["s"], st["p"], L.seeds, dA=st["dA"], dB=st["dB"],
-                                              workspace=st["ws"], dX=st.get("dX"))[0]
+            binding.multi_lora_bwd(st["X"], st["W"], st["A"], st["B"], st["S"], st["dY"], L.seg_offsets,
+                                   st["s"], st["p"], L.seeds, dA=st["dA"], dB=st["dB"],
+                                   workspace=st["ws"], dX=st["dX"])
 
     for _ in range(args.warmup):
         step()
@@ -164,6 +179,17 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
 
+    # spread of single steps: events on the launch stream (the binding launches on torch's current stream)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    evs[0].record()
+    for i in range(args.steps):
+        step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps))
+    step_ms = {"median": round(per_step[len(per_step) // 2], 4), "min": round(per_step[0], 4),
+               "max": round(per_step[-1], 4)}
+
     flops = sum(st["L"].flops for st in state)
     tokens = state[0]["L"].M                    # the layers of one configuration share the token batch
     fused_bytes = sum(st["L"].fused_bytes for st in state)
@@ -173,6 +199,7 @@ def main():
         print(json.dumps({"metric": "unfused multi-kernel LoRA linear fwd+bwd (baseline for comparison)",
                           "value": round(tflops, 2), "unit": "TFLOP/s", "ms_per_step": round(ms_per_step, 4),
                           "steps": args.steps, "warmup": args.warmup, "config": {"workload": args.workload},
+                          "step_ms": step_ms, "buffer_sets": len(sets),
                           "tokens_per_s": round(tokens / (ms_per_step * 1e-3), 1),
                           "algorithmic_hbm_bytes_per_token": round(sum(st["L"].unfused_bytes for st in state) / tokens, 1)}))
         return
@@ -211,6 +238,8 @@ def main():
         "config": {"workload": args.workload + ": " + ", ".join(
             f"{st['L'].name} M={st['L'].M} K={st['L'].K} N={st['L'].N} r={st['L'].r} G={st['L'].G} p={st['L'].p}"
             for st in state)},
+        "step_ms": step_ms,
+        "buffer_sets": len(sets),
         "tokens_per_s": round(tokens / (ms_per_step * 1e-3), 1),
         "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "algorithmic_hbm_bytes_per_token": round(fused_bytes / tokens, 1),
