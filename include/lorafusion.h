@@ -104,6 +104,29 @@ lora_status multi_lora_bwd(const lora_bf16* X, const lora_bf16* W, const lora_bf
                            lora_bf16* dX, float* dA, float* dB, int accumulate,
                            void* workspace, size_t workspace_bytes, lora_stream stream);
 
+/* Adapters of different rank in one packed batch (Section 5.1, FusedMultiLoRA: the lookup table holds
+ * each adapter's rank, scale and dropout).  ranks (host, G entries; NULL = every adapter has rank r)
+ * gives adapter g's rank, 16, 32 or 64 and at most r.  The arrays keep the uniform layout of the
+ * calls above with r as the allocated rank: A [G,r,K], B [G,N,r], S_saved [M,r], dA [G,r,K],
+ * dB [G,N,r]; adapter g uses rows 0..ranks[g]-1 of A[g] and columns 0..ranks[g]-1 of B[g].  The
+ * remaining rows / columns of A and B are ignored whatever they hold; the corresponding entries of
+ * S_saved, dA and dB are written as zeros (dA, dB: left untouched under accumulate).  Everything else
+ * as in multi_lora_fwd / multi_lora_bwd; the result for segment g equals a lora_fwd / lora_bwd call
+ * with r = ranks[g] on the compact arrays.  A rank outside {16,32,64} or above r:
+ * LORA_ERR_UNSUPPORTED. */
+lora_status multi_lora_fwd_ranked(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                                  int64_t M, int64_t K, int64_t N, int32_t r, int32_t G,
+                                  const int64_t* seg_offsets, const int32_t* ranks, const float* s,
+                                  const float* p, const uint64_t* seeds,
+                                  lora_bf16* Y, lora_bf16* S_saved, lora_stream stream);
+lora_status multi_lora_bwd_ranked(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                                  const lora_bf16* S_saved, const lora_bf16* dY,
+                                  int64_t M, int64_t K, int64_t N, int32_t r, int32_t G,
+                                  const int64_t* seg_offsets, const int32_t* ranks, const float* s,
+                                  const float* p, const uint64_t* seeds,
+                                  lora_bf16* dX, float* dA, float* dB, int accumulate,
+                                  void* workspace, size_t workspace_bytes, lora_stream stream);
+
 /* Diagnostic: writes keep(i,j) (1 = kept, 0 = dropped) for rows 0..M-1 and columns 0..K-1 of one
  * adapter into keep [M,K] (device, bytes).  Any M, K >= 0. */
 lora_status lora_debug_mask(int64_t M, int64_t K, float p, uint64_t seed, uint8_t* keep,

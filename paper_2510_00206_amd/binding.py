@@ -16,7 +16,8 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblorafusion_hip.so")
 
-EXPORTS = ("lora_fwd", "lora_bwd", "multi_lora_fwd", "multi_lora_bwd", "lora_bwd_workspace_bytes",
+EXPORTS = ("lora_fwd", "lora_bwd", "multi_lora_fwd", "multi_lora_bwd", "multi_lora_fwd_ranked",
+           "multi_lora_bwd_ranked", "lora_bwd_workspace_bytes",
            "lora_debug_mask", "lora_status_string", "lora_version",
            "lora_unfused_fwd", "lora_unfused_bwd", "lora_unfused_workspace_bytes")
 
@@ -39,6 +40,11 @@ def load_library() -> C.CDLL:
     lib.multi_lora_bwd.argtypes = [P, P, P, P, P, P, I64, I64, I64, I32, I32,
                                    C.POINTER(I64), C.POINTER(F), C.POINTER(F), C.POINTER(U64),
                                    P, P, P, C.c_int, P, SZ, P]
+    lib.multi_lora_fwd_ranked.argtypes = [P, P, P, P, I64, I64, I64, I32, I32, C.POINTER(I64), C.POINTER(I32),
+                                          C.POINTER(F), C.POINTER(F), C.POINTER(U64), P, P, P]
+    lib.multi_lora_bwd_ranked.argtypes = [P, P, P, P, P, P, I64, I64, I64, I32, I32, C.POINTER(I64), C.POINTER(I32),
+                                          C.POINTER(F), C.POINTER(F), C.POINTER(U64),
+                                          P, P, P, C.c_int, P, SZ, P]
     lib.lora_bwd_workspace_bytes.argtypes = [I64, I64, I64, I32, I32]
     lib.lora_bwd_workspace_bytes.restype = SZ
     lib.lora_debug_mask.argtypes = [I64, I64, F, U64, P, P]
@@ -56,7 +62,8 @@ def load_library() -> C.CDLL:
     lib.lora_unfused_fwd.restype = C.c_int
     lib.lora_unfused_bwd.restype = C.c_int
     lib.lora_profile_end.argtypes = [C.POINTER(F), C.POINTER(I32)]
-    for f in ("lora_fwd", "lora_bwd", "multi_lora_fwd", "multi_lora_bwd", "lora_debug_mask",
+    for f in ("lora_fwd", "lora_bwd", "multi_lora_fwd", "multi_lora_bwd", "multi_lora_fwd_ranked",
+              "multi_lora_bwd_ranked", "lora_debug_mask",
               "lora_profile_begin", "lora_profile_end"):
         getattr(lib, f).restype = C.c_int
     _lib = lib
@@ -124,12 +131,19 @@ def lora_bwd(X, W, A, B, S, dY, s, p, seed, need_dx=True, dA=None, dB=None, accu
     return dX, dA, dB
 
 
-def multi_lora_fwd(X, W, A, B, seg_offsets: Sequence[int], s, p, seeds, Y=None, S=None):
-    """Packed mixed-adapter forward.  A [G,r,K], B [G,N,r]; seg_offsets, s, p, seeds are host lists."""
+def multi_lora_fwd(X, W, A, B, seg_offsets: Sequence[int], s, p, seeds, Y=None, S=None, ranks=None):
+    """Packed mixed-adapter forward.  A [G,r,K], B [G,N,r]; seg_offsets, s, p, seeds are host lists;
+    ranks (optional host list): per-adapter rank <= r, the arrays keep r as the allocated rank."""
     M, K = X.shape
     G, N, r = B.shape
     Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device) if Y is None else Y
     S = torch.empty((M, r), dtype=torch.bfloat16, device=X.device) if S is None else S
+    if ranks is not None:
+        _check(load_library().multi_lora_fwd_ranked(
+            _ptr(X), _ptr(W), _ptr(A), _ptr(B), M, K, N, r, G,
+            _arr(C.c_int64, list(seg_offsets)), _arr(C.c_int32, list(ranks)), _arr(C.c_float, list(s)),
+            _arr(C.c_float, list(p)), _arr(C.c_uint64, list(seeds)), _ptr(Y), _ptr(S), _stream()))
+        return Y, S
     _check(load_library().multi_lora_fwd(
         _ptr(X), _ptr(W), _ptr(A), _ptr(B), M, K, N, r, G,
         _arr(C.c_int64, list(seg_offsets)), _arr(C.c_float, list(s)), _arr(C.c_float, list(p)),
@@ -138,7 +152,7 @@ def multi_lora_fwd(X, W, A, B, seg_offsets: Sequence[int], s, p, seeds, Y=None, 
 
 
 def multi_lora_bwd(X, W, A, B, S, dY, seg_offsets, s, p, seeds, need_dx=True, dA=None, dB=None,
-                   accumulate=False, workspace=None, dX=None):
+                   accumulate=False, workspace=None, dX=None, ranks=None):
     """dX [M,K] bf16 (or None), dA [G,r,K] fp32, dB [G,N,r] fp32."""
     M, K = X.shape
     G, N, r = B.shape
@@ -148,6 +162,13 @@ def multi_lora_bwd(X, W, A, B, S, dY, seg_offsets, s, p, seeds, need_dx=True, dA
     dA = torch.empty((G, r, K), dtype=torch.float32, device=X.device) if dA is None else dA
     dB = torch.empty((G, N, r), dtype=torch.float32, device=X.device) if dB is None else dB
     ws = alloc_workspace(M, K, N, r, G, X.device) if workspace is None else workspace
+    if ranks is not None:
+        _check(load_library().multi_lora_bwd_ranked(
+            _ptr(X), _ptr(W), _ptr(A), _ptr(B), _ptr(S), _ptr(dY), M, K, N, r, G,
+            _arr(C.c_int64, list(seg_offsets)), _arr(C.c_int32, list(ranks)), _arr(C.c_float, list(s)),
+            _arr(C.c_float, list(p)), _arr(C.c_uint64, list(seeds)), _ptr(dX), _ptr(dA), _ptr(dB), int(accumulate),
+            _ptr(ws), ws.numel(), _stream()))
+        return dX, dA, dB
     _check(load_library().multi_lora_bwd(
         _ptr(X), _ptr(W), _ptr(A), _ptr(B), _ptr(S), _ptr(dY), M, K, N, r, G,
         _arr(C.c_int64, list(seg_offsets)), _arr(C.c_float, list(s)), _arr(C.c_float, list(p)),

@@ -38,10 +38,16 @@ lora_status fill_adapter(AdapterTable& tb, int g, float s, float p, uint64_t see
     return LORA_OK;
 }
 
-lora_status build_table(AdapterTable& tb, int64_t M, int32_t G, const int64_t* off, const float* s,
-                        const float* p, const uint64_t* seeds) {
+// ranks == NULL: every adapter has the call's rank r
+lora_status build_table(AdapterTable& tb, int64_t M, int32_t r, int32_t G, const int64_t* off, const float* s,
+                        const float* p, const uint64_t* seeds, const int32_t* ranks) {
     memset(&tb, 0, sizeof(tb));
     tb.G = G;
+    for (int g = 0; g < G; ++g) {
+        const int32_t rg = ranks ? ranks[g] : r;
+        if (!(rg == 16 || rg == 32 || rg == 64) || rg > r) return LORA_ERR_UNSUPPORTED;
+        tb.rank[g] = (uint8_t)rg;
+    }
     if (off[0] != 0 || off[G] != M) return LORA_ERR_SEGMENTS;
     for (int g = 0; g < G; ++g)
         if (off[g + 1] < off[g]) return LORA_ERR_SEGMENTS;
@@ -128,10 +134,10 @@ size_t lora_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N, int32_t r, int3
     return carve(nullptr, M, K, N, r, G).bytes;
 }
 
-lora_status multi_lora_fwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
-                           int64_t M, int64_t K, int64_t N, int32_t r, int32_t G,
-                           const int64_t* seg_offsets, const float* s, const float* p, const uint64_t* seeds,
-                           lora_bf16* Y, lora_bf16* S_saved, lora_stream stream) {
+lora_status multi_lora_fwd_ranked(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                                  int64_t M, int64_t K, int64_t N, int32_t r, int32_t G,
+                                  const int64_t* seg_offsets, const int32_t* ranks, const float* s, const float* p,
+                                  const uint64_t* seeds, lora_bf16* Y, lora_bf16* S_saved, lora_stream stream) {
     // with M == 0 the token-sized arrays are empty and may be NULL
     if (!W || !A || !B || !seg_offsets || !s || !p || !seeds) return LORA_ERR_NULL;
     if (M != 0 && (!X || !Y || !S_saved)) return LORA_ERR_NULL;
@@ -140,10 +146,17 @@ lora_status multi_lora_fwd(const lora_bf16* X, const lora_bf16* W, const lora_bf
     if (misaligned(X) || misaligned(W) || misaligned(A) || misaligned(B) || misaligned(Y) || misaligned(S_saved))
         return LORA_ERR_ALIGN;
     AdapterTable tb;
-    st = build_table(tb, M, G, seg_offsets, s, p, seeds);
+    st = build_table(tb, M, r, G, seg_offsets, s, p, seeds, ranks);
     if (st != LORA_OK) return st;
     if (M == 0) return LORA_OK;
     return fwd_impl(X, W, A, B, M, K, N, r, tb, Y, S_saved, (hipStream_t)stream);
+}
+
+lora_status multi_lora_fwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                           int64_t M, int64_t K, int64_t N, int32_t r, int32_t G,
+                           const int64_t* seg_offsets, const float* s, const float* p, const uint64_t* seeds,
+                           lora_bf16* Y, lora_bf16* S_saved, lora_stream stream) {
+    return multi_lora_fwd_ranked(X, W, A, B, M, K, N, r, G, seg_offsets, nullptr, s, p, seeds, Y, S_saved, stream);
 }
 
 lora_status lora_fwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
@@ -153,12 +166,12 @@ lora_status lora_fwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A,
     return multi_lora_fwd(X, W, A, B, M, K, N, r, 1, off, &s, &p, &seed, Y, S_saved, stream);
 }
 
-lora_status multi_lora_bwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
-                           const lora_bf16* S_saved, const lora_bf16* dY,
-                           int64_t M, int64_t K, int64_t N, int32_t r, int32_t G,
-                           const int64_t* seg_offsets, const float* s, const float* p, const uint64_t* seeds,
-                           lora_bf16* dX, float* dA, float* dB, int accumulate,
-                           void* workspace, size_t workspace_bytes, lora_stream stream) {
+lora_status multi_lora_bwd_ranked(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                                  const lora_bf16* S_saved, const lora_bf16* dY,
+                                  int64_t M, int64_t K, int64_t N, int32_t r, int32_t G,
+                                  const int64_t* seg_offsets, const int32_t* ranks, const float* s, const float* p,
+                                  const uint64_t* seeds, lora_bf16* dX, float* dA, float* dB, int accumulate,
+                                  void* workspace, size_t workspace_bytes, lora_stream stream) {
     if (!W || !A || !B || !dA || !dB || !workspace || !seg_offsets || !s || !p || !seeds) return LORA_ERR_NULL;
     if (M != 0 && (!X || !S_saved || !dY)) return LORA_ERR_NULL;
     lora_status st = check_shape(M, K, N, r, G);
@@ -167,11 +180,21 @@ lora_status multi_lora_bwd(const lora_bf16* X, const lora_bf16* W, const lora_bf
         misaligned(dY) || misaligned(dA) || misaligned(dB) || (dX && misaligned(dX)) || misaligned(workspace, 256))
         return LORA_ERR_ALIGN;
     AdapterTable tb;
-    st = build_table(tb, M, G, seg_offsets, s, p, seeds);
+    st = build_table(tb, M, r, G, seg_offsets, s, p, seeds, ranks);
     if (st != LORA_OK) return st;
     if (workspace_bytes < carve(nullptr, M, K, N, r, G).bytes) return LORA_ERR_WORKSPACE;
     return bwd_impl(X, W, A, B, S_saved, dY, M, K, N, r, tb, dX, dA, dB, accumulate, workspace,
                     (hipStream_t)stream);
+}
+
+lora_status multi_lora_bwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                           const lora_bf16* S_saved, const lora_bf16* dY,
+                           int64_t M, int64_t K, int64_t N, int32_t r, int32_t G,
+                           const int64_t* seg_offsets, const float* s, const float* p, const uint64_t* seeds,
+                           lora_bf16* dX, float* dA, float* dB, int accumulate,
+                           void* workspace, size_t workspace_bytes, lora_stream stream) {
+    return multi_lora_bwd_ranked(X, W, A, B, S_saved, dY, M, K, N, r, G, seg_offsets, nullptr, s, p, seeds, dX, dA, dB,
+                                 accumulate, workspace, workspace_bytes, stream);
 }
 
 lora_status lora_bwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,

@@ -26,6 +26,10 @@ struct AdapterTable {
     uint32_t k1[kMaxAdapters];
     float s[kMaxAdapters];        // the paper's alpha
     float q[kMaxAdapters];        // survivor scale 65536/(65536-T)
+    // rank of adapter g (16, 32 or 64), at most the call's r: the arrays are laid out with r columns
+    // (rows of A) per adapter and adapter g uses the first rank[g]; the padding of A and B is never used
+    // and the padding of S', dS, dA and dB is written as zeros
+    uint8_t rank[kMaxAdapters];
 };
 
 // A row tile: `rows` valid rows starting at global row `row_start`, owned by adapter g.

@@ -22,6 +22,7 @@ __global__ void __launch_bounds__(DOWN_WAVES * 64) down_kernel(DownArgs p) {
     const int g = rt.g;
     const KeepThreshold T = keep_threshold(p.tb.T[g]);
     const lora_bf16* Ag = p.A + (int64_t)g * p.r * p.K;
+    const int cbn = p.tb.rank[g] >> 4;                  // 16-column blocks this adapter uses (<= CB)
 
     const lora_bf16* xrow[2];
     RowKey rk[2];
@@ -53,7 +54,8 @@ __global__ void __launch_bounds__(DOWN_WAVES * 64) down_kernel(DownArgs p) {
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) c.x[rb] = *(const u32x4*)(xrow[rb] + col);
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) c.a[cb] = *(const u32x4*)(Ag + (int64_t)(cb * 16 + (l & 15)) * p.K + col);
+        for (int cb = 0; cb < CB; ++cb)
+            if (CB == 1 || cb < cbn) c.a[cb] = *(const u32x4*)(Ag + (int64_t)(cb * 16 + (l & 15)) * p.K + col);
     };
     auto consume = [&](const ChunkRegs& c, int kc0) {
         const int kc = (kc0 + rot) % nchunks;
@@ -63,7 +65,7 @@ __global__ void __launch_bounds__(DOWN_WAVES * 64) down_kernel(DownArgs p) {
             const bf16x8 xf = __builtin_bit_cast(bf16x8, mask8(c.x[rb], rk[rb], col, T));
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
-                acc[rb][cb] = LF_MFMA16(__builtin_bit_cast(bf16x8, c.a[cb]), xf, acc[rb][cb]);
+                if (CB == 1 || cb < cbn) acc[rb][cb] = LF_MFMA16(__builtin_bit_cast(bf16x8, c.a[cb]), xf, acc[rb][cb]);
         }
     };
 #pragma unroll

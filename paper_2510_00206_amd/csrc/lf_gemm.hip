@@ -324,7 +324,7 @@ __device__ __forceinline__ int group_adapter(const GroupMap& gm, int q) {
 // with ordinary stores (zeros cannot come from a global->LDS copy); returns the number of sub-steps.
 __device__ __forceinline__ int build_mixed_lora_slabs(char* smem, int lo, const lora_bf16* S_tile,
                                                       const lora_bf16* B, int N, int n0, int r, int rows_valid,
-                                                      int cols_valid, const GroupMap& gm) {
+                                                      int cols_valid, const GroupMap& gm, const AdapterTable& tb) {
     const int nq = (rows_valid + 63) >> 6;
     int run_of_q[4], g_of_run[4];
     int nruns = 1;
@@ -340,6 +340,9 @@ __device__ __forceinline__ int build_mixed_lora_slabs(char* smem, int lo, const 
         }
         run_of_q[q] = nruns - 1;
     }
+    int rank_of_run[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) rank_of_run[j] = tb.rank[g_of_run[j]];
     const int rc = r >> 3;                               // 16-byte chunks per adapter block: 2, 4 or 8
     const int rc_shift = rc == 2 ? 1 : rc == 4 ? 2 : 3;
     __syncthreads();                                     // every wave is done with both stages
@@ -350,8 +353,9 @@ __device__ __forceinline__ int build_mixed_lora_slabs(char* smem, int lo, const 
         const int q = row >> 6;
         const int rq = q == 0 ? run_of_q[0] : q == 1 ? run_of_q[1] : q == 2 ? run_of_q[2] : run_of_q[3];
         const int gj = j == 0 ? g_of_run[0] : j == 1 ? g_of_run[1] : j == 2 ? g_of_run[2] : g_of_run[3];
+        const int rank_j = j == 0 ? rank_of_run[0] : j == 1 ? rank_of_run[1] : j == 2 ? rank_of_run[2] : rank_of_run[3];
         u32x4 tv = {0u, 0u, 0u, 0u}, bv = {0u, 0u, 0u, 0u};
-        if (j < nruns) {
+        if (j < nruns && sub * 8 < rank_j) {             // columns past the adapter's own rank stay zero
             if (rq == j) tv = *(const u32x4*)(S_tile + (int64_t)min(row, rows_valid - 1) * r + sub * 8);
             bv = *(const u32x4*)(B + ((int64_t)gj * N + n0 + min(row, cols_valid - 1)) * r + sub * 8);
         }
@@ -428,10 +432,10 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     }
     if (has_lora) {
         const int lo = (nk & 1) * STAGE_BYTES;         // the stage that holds the LoRA slab
-        int nkk = p.r / 16;
+        int nkk = p.tb.rank[rt.g] >> 4;
         if (gm.mixed) {
             // a tile with several adapters: both stages are rebuilt as one wide LoRA slab pair (below)
-            nkk = build_mixed_lora_slabs(smem, lo, Ssrc, p.B, p.N, n0, p.r, rt.rows, cols_valid, gm);
+            nkk = build_mixed_lora_slabs(smem, lo, Ssrc, p.B, p.N, n0, p.r, rt.rows, cols_valid, gm, p.tb);
             read_frags<false>(f0, smem + lo + tok_org, smem + lo + out_org, fl, fl.row_off[0], 0);
         }
         mma_frags<0, 4>(acc, f0);
@@ -498,7 +502,6 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
         // mixed).  Within a run, one 32x32 block at a time: t = dS A^T on a fresh accumulator, masked and
         // scaled, becomes the block's starting value; the hash of a block overlaps the next block's MFMAs.
         const int l = threadIdx.x & 63;
-        const int nkk = p.r / 16;
         const char* lds_tok = smem + STAGE_BYTES + tok_org;
         const char* lds_out = smem + STAGE_BYTES + out_org;
         const uint32_t cp0 = (uint32_t)(j0 + wn * 128 + 4 * (l >> 5)) >> 1;     // this lane's first column pair
@@ -514,6 +517,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
                 __syncthreads();
             }
             const uint32_t T = p.tb.T[g];
+            const int nkk = p.tb.rank[g] >> 4;
             const float qs = p.tb.q[g];
             const uint32_t k0 = p.tb.k0[g], k1 = p.tb.k1[g];
             const int lrow0 = rt.row_start - p.tb.row0[g];        // tile row -> row inside the adapter's segment

@@ -55,6 +55,10 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     const int g = rt.g;
     const KeepThreshold T = keep_threshold(p.tb.T[g]);
     const uint32_t hk0 = p.tb.k0[g], hk1 = p.tb.k1[g];
+    const int rank_g = p.tb.rank[g], cbn = rank_g >> 4;       // columns / 16-column blocks this adapter uses
+    // Blocks past the adapter's rank hold zeros (S', dS and the staged B are zero there), so skipping
+    // their MFMAs is only a saving; the rank-64 dS+dB variant has no register to spare for the test.
+    constexpr bool RANK_SKIP = CB > 1 && !(CB == 4 && !IS_DA);    // CB == 1: the rank can only be 16
     // either output may be switched off (null pointer): the unfused baseline runs them as separate passes
     const bool do_red = p.part_out != nullptr, do_ds = !IS_DA && p.part_ds != nullptr;
 
@@ -110,7 +114,7 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
         for (int idx = t; idx < kStreamChunk * RCH; idx += ST_THREADS) {
             const int row = idx / RCH, ch = idx - row * RCH;
             u32x4 v = u32x4{0u, 0u, 0u, 0u};
-            if (row < cols_valid) v = *(const u32x4*)(Bg + (int64_t)row * R + ch * 8);
+            if (row < cols_valid && ch * 8 < rank_g) v = *(const u32x4*)(Bg + (int64_t)row * R + ch * 8);
             *(u32x4*)(lds_b + tile_off(row, ch, RCH)) = v;
         }
     };
@@ -130,8 +134,9 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
                 const bf16x8 fb = read_panel_tr_frag(lds_big, r0, w * 64 + jb * 16);
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb)
-                    acc[jb][cb] = IS_DA ? LF_MFMA16(fb, fs[cb], acc[jb][cb])     // D[j][c]
-                                        : LF_MFMA16(fs[cb], fb, acc[jb][cb]);    // D[c][n]
+                    if (!RANK_SKIP || cb < cbn)
+                        acc[jb][cb] = IS_DA ? LF_MFMA16(fb, fs[cb], acc[jb][cb])     // D[j][c]
+                                            : LF_MFMA16(fs[cb], fb, acc[jb][cb]);    // D[c][n]
             }
         }
 
@@ -148,6 +153,7 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
                 const bf16x8 ft = __builtin_bit_cast(bf16x8, tv);
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) {
+                    if (RANK_SKIP && cb >= cbn) continue;
                     const bf16x8 fbm = read_tr_frag(lds_b, ncol + 8 * (l >> 4), cb * 16, RCH);
                     ads[cb] = LF_MFMA16(fbm, ft, ads[cb]);         // D[c][i]
                 }

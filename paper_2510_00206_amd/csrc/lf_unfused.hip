@@ -111,11 +111,12 @@ bool supported(int64_t M, int64_t K, int64_t N, int32_t r) {
 }
 
 // one adapter over all rows; `plain` switches dropout off and all scales to one
-AdapterTable make_table(int64_t M, float s, float p, uint64_t seed, bool plain) {
+AdapterTable make_table(int64_t M, int32_t r, float s, float p, uint64_t seed, bool plain) {
     AdapterTable tb;
     memset(&tb, 0, sizeof(tb));
     tb.G = 1;
     tb.row0[1] = (int)M;
+    tb.rank[0] = (uint8_t)r;
     const double t = floor((double)p * 65536.0);
     const uint32_t T = plain ? 0u : (t > 65535.0 ? 65535u : (uint32_t)t);
     tb.T[0] = T;
@@ -147,7 +148,7 @@ lora_status lora_unfused_fwd(const lora_bf16* X, const lora_bf16* W, const lora_
     const UWorkspace ws = carve(workspace, M, K, N, r);
     if (workspace_bytes < ws.bytes) return LORA_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    const AdapterTable real = make_table(M, s, p, seed, false), plain = make_table(M, s, p, seed, true);
+    const AdapterTable real = make_table(M, r, s, p, seed, false), plain = make_table(M, r, s, p, seed, true);
     // 1. Xhat = dropout(X)
     hipLaunchKernelGGL(dropout_kernel, dim3(blocks_for(M * (K >> 3))), dim3(EW_THREADS), 0, st, X, ws.Xhat, M, (int)K,
                        real.T[0], real.q[0], real.k0[0], real.k1[0]);
@@ -177,7 +178,7 @@ lora_status lora_unfused_bwd(const lora_bf16* W, const lora_bf16* A, const lora_
     const UWorkspace ws = carve(workspace, M, K, N, r);
     if (workspace_bytes < ws.bytes) return LORA_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    const AdapterTable real = make_table(M, s, p, seed, false), plain = make_table(M, s, p, seed, true);
+    const AdapterTable real = make_table(M, r, s, p, seed, false), plain = make_table(M, r, s, p, seed, true);
     const int chunks = (int)((N + kStreamChunk - 1) / kStreamChunk);
     // 1. dY2 = s dY
     hipLaunchKernelGGL(scale_kernel, dim3(blocks_for(M * N / 8)), dim3(EW_THREADS), 0, st, dY, ws.dY2, M * N / 8, s);
@@ -211,7 +212,7 @@ lora_status lora_frozen_fwd(const lora_bf16* X, const lora_bf16* W, int64_t M, i
                             lora_stream stream) {
     if (!X || !W || !Y) return LORA_ERR_NULL;
     if (!supported(M, K, N, 16)) return LORA_ERR_UNSUPPORTED;
-    const AdapterTable plain = make_table(M, 1.f, 0.f, 0, true);
+    const AdapterTable plain = make_table(M, 0, 1.f, 0.f, 0, true);
     LF_TRY(launch_fwd_gemm(FwdGemmArgs{X, W, nullptr, nullptr, Y, (int)M, (int)K, (int)N, 0, 0, 0, plain}, (hipStream_t)stream));
     return LORA_OK;
 }
@@ -220,7 +221,7 @@ lora_status lora_frozen_bwd(const lora_bf16* dY, const lora_bf16* W, int64_t M, 
                             lora_stream stream) {
     if (!dY || !W || !dX) return LORA_ERR_NULL;
     if (!supported(M, K, N, 16)) return LORA_ERR_UNSUPPORTED;
-    const AdapterTable plain = make_table(M, 1.f, 0.f, 0, true);
+    const AdapterTable plain = make_table(M, 0, 1.f, 0.f, 0, true);
     LF_TRY(launch_bwd_dx(DxGemmArgs{dY, W, nullptr, nullptr, dX, (int)M, (int)K, (int)N, 0, 0, 0, plain}, (hipStream_t)stream));
     return LORA_OK;
 }

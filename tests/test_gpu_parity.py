@@ -217,3 +217,59 @@ def test_empty_batch_and_many_adapters():
         binding.multi_lora_fwd(gpu["Y"].new_empty((L.M, 192)), W[:, :192].contiguous(), inp[2].cuda().repeat(2, 1, 1)[:65],
                                inp[3].cuda().repeat(2, 1, 1)[:65], list(range(0, 65)) + [L.M], [1.0] * 65, [0.1] * 65, [1] * 65)
     assert e.value.status in (5, 7)
+
+
+HETERO = [  # M, K, N, allocated r, segment lengths, ranks
+    (832, 256, 320, 64, (192, 64, 128, 448), (16, 64, 32, 16)),          # boundaries on 64: tiles with several adapters
+    (601, 320, 192, 32, (100, 37, 300, 164), (32, 16, 16, 32)),          # boundaries off the 64 grid
+    (768, 192, 448, 64, (64, 64, 128, 0, 512), (32, 16, 64, 16, 32)),    # three ranks inside one row tile
+]
+
+
+@pytest.mark.parametrize("case", HETERO, ids=lambda c: "x".join(str(v) for v in c[:4]))
+def test_heterogeneous_rank(case):
+    """Adapters of different rank in one packed batch (arrays allocated at the largest rank): every
+    segment equals the single-adapter call at its own rank on the compact arrays, bit for bit, and the
+    oracle run per segment; padding of A and B is never used (it holds NaN here) and the padding of
+    S', dA and dB comes out as zeros."""
+    M, K, N, r, lens, ranks = case
+    L = workloads.custom_layer(M, K, N, r, 2.0, 0.1, seg_lens=lens, cfg=8)
+    print(f"hetero rank {L} ranks={ranks}", flush=True)
+    X, W, A, B, dY = workloads.make_inputs(L)
+    A, B = A.clone(), B.clone()
+    for g, rg in enumerate(ranks):
+        A[g, rg:] = float("nan")
+        B[g, :, rg:] = float("nan")
+    s = [0.5 + g for g in range(L.G)]
+    p = [0.05 * (g + 1) for g in range(L.G)]
+    dev = "cuda"
+    Xg, Wg, Ag, Bg, dYg = (t.to(dev) for t in (X, W, A, B, dY))
+    Y, S = binding.multi_lora_fwd(Xg, Wg, Ag, Bg, L.seg_offsets, s, p, L.seeds, ranks=ranks)
+    dX, dA, dB = binding.multi_lora_bwd(Xg, Wg, Ag, Bg, S, dYg, L.seg_offsets, s, p, L.seeds, ranks=ranks)
+    torch.cuda.synchronize()
+    o = L.seg_offsets
+    for g, rg in enumerate(ranks):
+        sl = slice(o[g], o[g + 1])
+        assert not S[sl, rg:].any() and torch.isfinite(S[sl]).all()
+        if o[g + 1] == o[g]:
+            assert not dA[g].any() and not dB[g].any()
+            continue
+        assert not dA[g, rg:].any() and not dB[g, :, rg:].any()
+        Ac, Bc = Ag[g, :rg].contiguous(), Bg[g, :, :rg].contiguous()
+        # oracle on the compact adapter
+        Yr, Sr = oracle.lora_fwd(f64(X[sl]), f64(W), f64(A[g, :rg]), f64(B[g, :, :rg]), s[g], p[g], L.seeds[g])
+        dXr, dAr, dBr, _ = oracle.lora_bwd(f64(X[sl]), f64(W), f64(A[g, :rg]), f64(B[g, :, :rg]), f64(dY[sl]),
+                                           s[g], p[g], L.seeds[g])
+        compare(dict(Y=Y[sl], S=S[sl, :rg], dX=dX[sl], dA=dA[g, :rg], dB=dB[g, :, :rg]),
+                dict(Y=Yr, S=Sr * float(np.float32(s[g])), dX=dXr, dA=dAr, dB=dBr), label=f"hetero {case} g={g}")
+        # the single-adapter entry point at rank rg
+        Y1, S1 = binding.lora_fwd(Xg[sl].contiguous(), Wg, Ac, Bc, s[g], p[g], L.seeds[g])
+        dX1, dA1, dB1 = binding.lora_bwd(Xg[sl].contiguous(), Wg, Ac, Bc, S1, dYg[sl].contiguous(), s[g], p[g], L.seeds[g])
+        assert torch.equal(Y1, Y[sl]) and torch.equal(S1, S[sl, :rg]) and torch.equal(dX1, dX[sl])
+        assert torch.equal(dA1, dA[g, :rg]) and torch.equal(dB1, dB[g, :, :rg])
+    with pytest.raises(binding.LoraError) as e:        # a rank above the allocated one
+        binding.multi_lora_fwd(Xg, Wg, Ag, Bg, L.seg_offsets, s, p, L.seeds, ranks=[2 * r] + list(ranks[1:]))
+    assert e.value.status == 7
+    with pytest.raises(binding.LoraError) as e:
+        binding.multi_lora_fwd(Xg, Wg, Ag, Bg, L.seg_offsets, s, p, L.seeds, ranks=[24] + list(ranks[1:]))
+    assert e.value.status == 7
