@@ -82,6 +82,29 @@ CONFIGS = {
 }
 
 
+def _decoder_layer(tag: str, cfg: int, M: int, hidden: int, kv: int, ffn: int, fuse_qkv: bool) -> List[Layer]:
+    """The seven LoRA linears of one decoder layer, back to back (the paper's layer-wise comparison,
+    Section 6.4): q, k, v, o, gate, up, down.  With fuse_qkv the three projections that share the input
+    run as ONE LoRA linear: W = [Wq; Wk; Wv] (N = hidden + 2 kv), A = [Aq; Ak; Av; 0] (rank 3*16 padded
+    to 64) and B block-diagonal, so that one pass of operation (1) over X serves all three adapters
+    (they then share one dropout mask).  Timing does not depend on B's zero blocks."""
+    r, s, p = 16, 2.0, 0.1
+    if fuse_qkv:
+        head = [Layer(f"{tag}_qkv", cfg, M, hidden, hidden + 2 * kv, 64, s, p)]
+    else:
+        head = [Layer(f"{tag}_q", cfg, M, hidden, hidden, r, s, p), Layer(f"{tag}_k", cfg, M, hidden, kv, r, s, p),
+                Layer(f"{tag}_v", cfg, M, hidden, kv, r, s, p)]
+    return head + [Layer(f"{tag}_o", cfg, M, hidden, hidden, r, s, p), Layer(f"{tag}_gate", cfg, M, hidden, ffn, r, s, p),
+                   Layer(f"{tag}_up", cfg, M, hidden, ffn, r, s, p), Layer(f"{tag}_down", cfg, M, ffn, hidden, r, s, p)]
+
+
+# Decoder-layer composites (8B- and 70B-style shapes, 8192 resp. 4096 tokens).
+CONFIGS["layer8b"] = _decoder_layer("l8b", 11, 8192, 4096, 1024, 14336, False)
+CONFIGS["layer8b_qkv"] = _decoder_layer("l8b", 11, 8192, 4096, 1024, 14336, True)
+CONFIGS["layer70b"] = _decoder_layer("l70b", 12, 4096, 8192, 1024, 28672, False)
+CONFIGS["layer70b_qkv"] = _decoder_layer("l70b", 12, 4096, 8192, 1024, 28672, True)
+
+
 def _gen(seed: int) -> torch.Generator:
     g = torch.Generator(device="cpu")
     g.manual_seed(seed)

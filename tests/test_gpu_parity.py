@@ -273,3 +273,42 @@ def test_heterogeneous_rank(case):
     with pytest.raises(binding.LoraError) as e:
         binding.multi_lora_fwd(Xg, Wg, Ag, Bg, L.seg_offsets, s, p, L.seeds, ranks=[24] + list(ranks[1:]))
     assert e.value.status == 7
+
+
+def test_fused_qkv_as_one_lora_linear():
+    """Three projections that share their input (q, k, v of a decoder layer) run as one LoRA linear with
+    W = [Wq; Wk; Wv], A = [Aq; Ak; Av; 0] and a block-diagonal B: with one dropout seed the forward
+    equals the three separate calls bit for bit, dA and the diagonal blocks of dB too, and dX is the sum
+    of the three input gradients (checked against the oracle's sum)."""
+    M, K, r = 320, 256, 16
+    Ns = (256, 64, 64)
+    s, p, seed = 2.0, 0.1, 77
+    dev = "cuda"
+    parts = [workloads.make_inputs(workloads.custom_layer(M, K, n, r, s, p, cfg=13), layer_index=i) for i, n in enumerate(Ns)]
+    X = parts[0][0]
+    Wc = torch.cat([q[1] for q in parts])
+    dYc = torch.cat([q[4] for q in parts], dim=1).contiguous()
+    Ac = torch.zeros((64, K), dtype=torch.bfloat16)
+    Bc = torch.zeros((sum(Ns), 64), dtype=torch.bfloat16)
+    n0 = 0
+    for i, (q, n) in enumerate(zip(parts, Ns)):
+        Ac[16 * i:16 * i + 16] = q[2][0]
+        Bc[n0:n0 + n, 16 * i:16 * i + 16] = q[3][0]
+        n0 += n
+    print("fused qkv", flush=True)
+    Xg = X.to(dev)
+    Y, S = binding.lora_fwd(Xg, Wc.to(dev), Ac.to(dev), Bc.to(dev), s, p, seed)
+    dX, dA, dB = binding.lora_bwd(Xg, Wc.to(dev), Ac.to(dev), Bc.to(dev), S, dYc.to(dev), s, p, seed)
+    torch.cuda.synchronize()
+    assert not S[:, 48:].any() and not dA[48:].any()
+    dX_ref = np.zeros((M, K))
+    n0 = 0
+    for i, (q, n) in enumerate(zip(parts, Ns)):
+        _, W, A, B, dY = q
+        Y1, S1 = binding.lora_fwd(Xg, W.to(dev), A[0].to(dev), B[0].to(dev), s, p, seed)
+        _, dA1, dB1 = binding.lora_bwd(Xg, W.to(dev), A[0].to(dev), B[0].to(dev), S1, dY.to(dev), s, p, seed)
+        assert torch.equal(Y1, Y[:, n0:n0 + n]) and torch.equal(S1, S[:, 16 * i:16 * i + 16])
+        assert torch.equal(dA1, dA[16 * i:16 * i + 16]) and torch.equal(dB1, dB[n0:n0 + n, 16 * i:16 * i + 16])
+        dX_ref += oracle.lora_bwd(f64(X), f64(W), f64(A[0]), f64(B[0]), f64(dY), s, p, seed)[0]
+        n0 += n
+    assert rel_err(dX, dX_ref) <= TOL
