@@ -126,11 +126,13 @@ __host__ __device__ __forceinline__ KeepThreshold keep_threshold(uint32_t T) {
 }
 
 __device__ __forceinline__ uint32_t keep_pair_mask(uint32_t w, KeepThreshold kt) {
-    typedef __attribute__((ext_vector_type(2))) unsigned short u16x2;
-    const u16x2 d = __builtin_elementwise_sub_sat(__builtin_bit_cast(u16x2, w), __builtin_bit_cast(u16x2, kt.tm1_packed));
-    const u16x2 one = {1, 1}, ffff = {0xFFFF, 0xFFFF};
-    const u16x2 m = __builtin_elementwise_min(d, one) * ffff;
-    return __builtin_bit_cast(uint32_t, m) | kt.keep_all;
+    // Three packed 16-bit instructions, written as such: from the generic form the compiler makes two
+    // compares, two selects and a byte permute per word.
+    uint32_t d, m;
+    asm("v_pk_sub_u16 %0, %1, %2 clamp" : "=v"(d) : "v"(w), "v"(kt.tm1_packed));
+    asm("v_pk_min_u16 %0, %1, %2" : "=v"(m) : "v"(d), "v"(0x00010001u));
+    asm("v_pk_mul_lo_u16 %0, %1, %2" : "=v"(d) : "v"(m), "v"(0xFFFFFFFFu));
+    return d | kt.keep_all;
 }
 
 // Mask 8 consecutive bf16 (columns col..col+7, col % 8 == 0) held in a 16-byte vector.

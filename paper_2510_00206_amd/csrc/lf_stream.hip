@@ -52,6 +52,7 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     const int c0 = chunk_id * kStreamChunk;
     const int cols_valid = min(kStreamChunk, p.C - c0);       // multiple of 64
     const int t = threadIdx.x, l = t & 63, w = t >> 6;
+    const int w_uniform = __builtin_amdgcn_readfirstlane(w);
     const int g = rt.g;
     const KeepThreshold T = keep_threshold(p.tb.T[g]);
     const uint32_t hk0 = p.tb.k0[g], hk1 = p.tb.k1[g];
@@ -72,30 +73,32 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     const lora_bf16* small_ = p.small_ + (int64_t)rt.row_start * R;
     const int nsteps = (rt.rows + ST_STEP - 1) / ST_STEP;
     const int bchunk = t & 63;                                // this thread's 16-byte chunk of a panel row
-    const bool col_ok = bchunk * 8 < cols_valid;
 
     struct StepRegs { u32x4 b[8], s; };
+    // Every load is issued unconditionally from a clamped address (rows past the end of the tile read its
+    // last row, columns past the end read the last valid chunk): with predicated loads the compiler cannot
+    // count what is in flight and waits for all of it - also the loads of the step after - before a step's
+    // data is used.  What the clamped lanes bring is multiplied by zero rows of the small operand (rows)
+    // or never stored (columns).
+    const int bchunk_ld = min(bchunk, (cols_valid >> 3) - 1);
     auto load_step = [&](StepRegs& rg, int step) {
         const int rows_left = rt.rows - step * ST_STEP;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int row = (t >> 6) + 8 * i;
-            rg.b[i] = u32x4{0u, 0u, 0u, 0u};
-            if (col_ok && row < rows_left)
-                rg.b[i] = *(const u32x4*)(big + (int64_t)(step * ST_STEP + row) * p.C + bchunk * 8);
+            const int row = min((t >> 6) + 8 * i, rows_left - 1);
+            rg.b[i] = *(const u32x4*)(big + (int64_t)(step * ST_STEP + row) * p.C + bchunk_ld * 8);
         }
-        rg.s = u32x4{0u, 0u, 0u, 0u};
-        if (t < ST_STEP * RCH) {
-            const int row = t / RCH, ch = t - row * RCH;
-            if (row < rows_left) rg.s = *(const u32x4*)(small_ + (int64_t)(step * ST_STEP + row) * R + ch * 8);
-        }
+        const int ts = min(t, ST_STEP * RCH - 1);
+        const int row = ts / RCH, ch = ts - row * RCH;
+        rg.s = *(const u32x4*)(small_ + (int64_t)(step * ST_STEP + min(row, rows_left - 1)) * R + ch * 8);
     };
     auto store_step = [&](const StepRegs& rg, int step) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int row = (t >> 6) + 8 * i;
+            const int row = w_uniform + 8 * i;
             u32x4 v = rg.b[i];
             if (IS_DA) {
+                // a wave stages one row per pass: the row's hash keys are formed on the scalar unit
                 const RowKey rk = row_key(hk0, hk1, (uint32_t)(rt.local_row0 + step * ST_STEP + row));
                 v = mask8(v, rk, (uint32_t)(c0 + bchunk * 8), T);
             }
@@ -103,7 +106,9 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
         }
         if (t < ST_STEP * RCH) {
             const int row = t / RCH, ch = t - row * RCH;
-            *(u32x4*)(lds_small + tile_off(row, ch, RCH)) = rg.s;
+            // rows past the end of the tile are zero in the small operand: they cancel the clamped rows
+            const u32x4 v = row < rt.rows - step * ST_STEP ? rg.s : u32x4{0u, 0u, 0u, 0u};
+            *(u32x4*)(lds_small + tile_off(row, ch, RCH)) = v;
         }
     };
 
@@ -184,6 +189,33 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     constexpr bool TWO_AHEAD = !(CB == 4 && !IS_DA);
     if constexpr (TWO_AHEAD) {
         StepRegs ra, rb2;
+        if (nsteps == 4) {
+            // full 256-row tile, written out as straight-line code: with the loads behind run-time
+            // conditions the compiler merges the in-flight counts of both paths and waits for everything
+            // before a step's data is used, which shortens the prefetch distance to one step
+            // (the scheduling barriers keep the loads where they are written: the scheduler otherwise
+            // sinks them towards their use)
+            load_step(ra, 0);
+            load_step(rb2, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            stage_b_chunk();                           // after the first panel loads are in flight
+            store_step(ra, 0);
+            __syncthreads();
+            load_step(ra, 2);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_step(0);
+            store_step(rb2, 1);
+            __syncthreads();
+            load_step(rb2, 3);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_step(1);
+            store_step(ra, 2);
+            __syncthreads();
+            compute_step(2);
+            store_step(rb2, 3);
+            __syncthreads();
+            compute_step(3);
+        } else {
         load_step(ra, 0);
         if (nsteps > 1) load_step(rb2, 1);
         stage_b_chunk();                               // after the first panel loads are in flight
@@ -198,6 +230,7 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
                 if (step + 3 < nsteps) load_step(rb2, step + 3);
                 compute_step(step + 1);
             }
+        }
         }
     } else {
         StepRegs ra;
