@@ -480,7 +480,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     const int tok_org = wm * 128 * 128, out_org = TILE_BYTES + wn * 128 * 2;
     const SlabLanes sd = row_slab_lanes(p.N, rt.rows, 8), sw = col_slab_lanes(p.K, BK, cols_valid);
 
-    // LoRA step first: acc = dS A^T, then the mask and q are applied to the accumulators and the
+    // LoRA step first: acc = dS A^T (dS arrives scaled by s*q), then the mask is applied to the accumulators and the
     // base-gradient contraction continues on top of them.
     // p.r == 0 (no LoRA term) and p.N == 0 (LoRA term only) serve the unfused baseline's plain GEMMs.
     const int nk = p.N / BK;
@@ -499,8 +499,8 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     __syncthreads();
     if (p.r > 0) {
         // One run of 64-row groups per adapter present in the tile (a single run unless the tile is
-        // mixed).  Within a run, one 32x32 block at a time: t = dS A^T on a fresh accumulator, masked and
-        // scaled, becomes the block's starting value; the hash of a block overlaps the next block's MFMAs.
+        // mixed).  Within a run, one 32x32 block at a time: t = dS A^T on a fresh accumulator, masked,
+        // becomes the block's starting value.
         const int l = threadIdx.x & 63;
         const char* lds_tok = smem + STAGE_BYTES + tok_org;
         const char* lds_out = smem + STAGE_BYTES + out_org;
@@ -518,7 +518,6 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
             }
             const uint32_t T = p.tb.T[g];
             const int nkk = p.tb.rank[g] >> 4;
-            const float qs = p.tb.q[g];
             const uint32_t k0 = p.tb.k0[g], k1 = p.tb.k1[g];
             const int lrow0 = rt.row_start - p.tb.row0[g];        // tile row -> row inside the adapter's segment
 #pragma unroll
@@ -540,16 +539,17 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
                             bf16x8, *(const u32x4*)(lds_tok + row_slab_off(l & 31, 2 * kk + (l >> 5)) + mi * 4096));
                         t = LF_MFMA(join_tr(lo, hi), ft, t);
                     }
+                    asm volatile("" : "+v"(t));              // in vector registers, where the selects below read it
 #pragma unroll
                     for (int g4 = 0; g4 < 4; ++g4) {
                         // columns ni*32 + 8*g4 + {0..3} past the lane's first column: pairs (ni*16 + 4*g4) + {0, 1}
                         const uint32_t w0 = hash_word_at(rk, x0 + (uint32_t)(ni * 16 + 4 * g4) * kGold);
                         const uint32_t w1 = hash_word_at(rk, x0 + (uint32_t)(ni * 16 + 4 * g4 + 1) * kGold);
                         f32x16& a = acc[mi][ni];
-                        a[4 * g4 + 0] = (w0 & 0xFFFFu) >= T ? t[4 * g4 + 0] * qs : 0.f;
-                        a[4 * g4 + 1] = (w0 >> 16) >= T ? t[4 * g4 + 1] * qs : 0.f;
-                        a[4 * g4 + 2] = (w1 & 0xFFFFu) >= T ? t[4 * g4 + 2] * qs : 0.f;
-                        a[4 * g4 + 3] = (w1 >> 16) >= T ? t[4 * g4 + 3] * qs : 0.f;
+                        a[4 * g4 + 0] = (w0 & 0xFFFFu) >= T ? t[4 * g4 + 0] : 0.f;
+                        a[4 * g4 + 1] = (w0 >> 16) >= T ? t[4 * g4 + 1] : 0.f;
+                        a[4 * g4 + 2] = (w1 & 0xFFFFu) >= T ? t[4 * g4 + 2] : 0.f;
+                        a[4 * g4 + 3] = (w1 >> 16) >= T ? t[4 * g4 + 3] : 0.f;
                     }
                     asm volatile("" : "+a"(acc[mi][ni]));    // the block is final here: nothing sinks past
                 }

@@ -302,14 +302,17 @@ hipError_t launch_stream_da(StreamArgs a, hipStream_t st) {
 }
 
 // ---- finalize: fixed-order sums of the partials ---------------------------------------------------
-// job 1: dS[i, c..c+3] = bf16(s_g * sum_chunks part_ds);  job 2: dB[g, n, c..c+3] (+)= sum over tiles of g
+// job 1: dS[i, c..c+3] = bf16(s_g * q_g * sum_chunks part_ds);  job 2: dB[g, n, c..c+3] (+)= sum over tiles of g
 __global__ void __launch_bounds__(256) finalize_ds_db_kernel(FinalizeArgs p, int blocks_ds) {
     const int r4 = p.r >> 2;
     if ((int)blockIdx.x < blocks_ds) {
         const int64_t idx = blockIdx.x * 256ll + threadIdx.x;
         if (idx >= (int64_t)p.M * r4) return;
         const int row = (int)(idx / r4);
-        const float s = p.tb.s[segment_of_row(p.tb, row)];
+        // dS leaves here scaled by s*q: the survivor scale q of the dropout that operations (4) and (5)
+        // owe their LoRA terms is applied once, to the small matrix, instead of per element of dA and dX
+        const int seg = segment_of_row(p.tb, row);
+        const float s = p.tb.s[seg] * p.tb.q[seg];
         f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
         for (int ch = 0; ch < p.chunks; ++ch) v += *(const f32x4*)(p.part_ds + ((int64_t)ch * p.M * r4 + idx) * 4);
@@ -335,7 +338,7 @@ __global__ void __launch_bounds__(256) finalize_ds_db_kernel(FinalizeArgs p, int
     }
 }
 
-// dA[g, c, j..j+3] (+)= q_g * sum over the row tiles of segment g
+// dA[g, c, j..j+3] (+)= sum over the row tiles of segment g (q_g is already in dS)
 __global__ void __launch_bounds__(256) finalize_da_kernel(FinalizeArgs p) {
     const int64_t per_g = (int64_t)p.r * (p.K >> 2);
     const int64_t idx = blockIdx.x * 256ll + threadIdx.x;
@@ -349,7 +352,6 @@ __global__ void __launch_bounds__(256) finalize_da_kernel(FinalizeArgs p) {
     f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
     for (int tl = tile0; tl < tile0 + nt; ++tl) v += *(const f32x4*)(p.part_da + ((int64_t)tl * per_g + e) * 4);
-    v *= p.tb.q[g];
     f32x4* out = (f32x4*)(p.dA + idx * 4);
     *out = p.accumulate ? *out + v : v;
 }
