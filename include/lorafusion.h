@@ -9,7 +9,7 @@
  * and its backward pass (dX, dA, dB), executed as the paper's five fused operations
  * (Section 5.1, "FusedLoRA Design"): (1) dropout + down-projection, (2) base GEMM + up-projection,
  * (3) dS together with dB, (4) dA, (5) dX = base gradient GEMM + masked LoRA gradient; and the
- * mixed-adapter form of the same operations (Section 5.1, "Extending to FusedMultiLoRA"), where
+ * mixed-adapter form of the same operations (Section 5.1, FusedMultiLoRA), where
  * contiguous row segments of a packed token batch belong to different adapters.
  *
  * Conventions shared by every entry point

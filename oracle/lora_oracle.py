@@ -14,7 +14,7 @@ What it follows
   does not print the equations; they are the chain rule applied to Eq. 1:
       dS = alpha * dY B^T,  dB = alpha * S^T dY,  dA = Xhat^T dS,
       dX = dY W^T + mask * q * (dS A^T)
-* Multi-adapter form (Section 5.1, "Extending to FusedMultiLoRA"): every token row belongs to
+* Multi-adapter form (Section 5.1, FusedMultiLoRA): every token row belongs to
   one adapter; the frozen product X W is shared, each contiguous row segment uses its own
   (A, B, alpha, dropout) and receives its own dA, dB.
 
