@@ -55,6 +55,90 @@ __device__ __forceinline__ bool find_row_tile(const AdapterTable& tb, int gran, 
     return false;
 }
 
+// Row panels of the streaming reductions (operations (3) and (4)).  A segment of length len holds
+// nf = len / gran full panels; a remainder is merged into the segment's last panel (a "long" panel of
+// fewer than 2*gran rows) or, when the segment is shorter than gran, forms one "short" panel.  Cutting
+// the remainder off as a panel of its own would add a workgroup per column chunk for a few rows and,
+// with the panel count just past a multiple of the CU count, a whole extra round of workgroups.
+// Panels are numbered long ones first (they run longest, so they start first), then the regular
+// ones, then the short ones; the number is also the plane index of the panel's partial sums.
+struct SegmentPanels { int nreg; bool has_long, has_short; int rem; };
+
+__host__ __device__ __forceinline__ SegmentPanels segment_panels(const AdapterTable& tb, int gran, int g) {
+    const int len = tb.row0[g + 1] - tb.row0[g];
+    const int nf = len / gran;
+    SegmentPanels sp;
+    sp.rem = len - nf * gran;
+    sp.has_short = nf == 0 && sp.rem > 0;
+    sp.has_long = nf > 0 && sp.rem > 0;
+    sp.nreg = nf - (sp.has_long ? 1 : 0);
+    return sp;
+}
+
+__host__ __device__ __forceinline__ int count_panels(const AdapterTable& tb, int gran) {
+    int n = 0;
+    for (int g = 0; g < tb.G; ++g) {
+        const SegmentPanels sp = segment_panels(tb, gran, g);
+        n += sp.nreg + (sp.has_long ? 1 : 0) + (sp.has_short ? 1 : 0);
+    }
+    return n;
+}
+
+__device__ __forceinline__ bool find_panel(const AdapterTable& tb, int gran, int panel, RowTile& rt) {
+    int idx = panel;
+    for (int g = 0; g < tb.G; ++g) {                     // long panels
+        const SegmentPanels sp = segment_panels(tb, gran, g);
+        if (!sp.has_long) continue;
+        if (idx == 0) {
+            rt.g = g;
+            rt.local_row0 = sp.nreg * gran;
+            rt.row_start = tb.row0[g] + rt.local_row0;
+            rt.rows = gran + sp.rem;
+            return true;
+        }
+        --idx;
+    }
+    for (int g = 0; g < tb.G; ++g) {                     // regular panels
+        const SegmentPanels sp = segment_panels(tb, gran, g);
+        if (idx < sp.nreg) {
+            rt.g = g;
+            rt.local_row0 = idx * gran;
+            rt.row_start = tb.row0[g] + rt.local_row0;
+            rt.rows = gran;
+            return true;
+        }
+        idx -= sp.nreg;
+    }
+    for (int g = 0; g < tb.G; ++g) {                     // short panels
+        const SegmentPanels sp = segment_panels(tb, gran, g);
+        if (!sp.has_short) continue;
+        if (idx == 0) {
+            rt.g = g;
+            rt.local_row0 = 0;
+            rt.row_start = tb.row0[g];
+            rt.rows = sp.rem;
+            return true;
+        }
+        --idx;
+    }
+    return false;
+}
+
+// Plane indices of segment g's panels: regular planes [reg0, reg0 + nreg), then `extra` (its long or
+// short panel, -1 if none).  The finalize kernels add them in exactly this order.
+__device__ __forceinline__ void segment_planes(const AdapterTable& tb, int gran, int g, int& reg0, int& nreg, int& extra) {
+    int n_long = 0, n_reg = 0, n_short = 0, long_before = 0, reg_before = 0, short_before = 0;
+    for (int gg = 0; gg < tb.G; ++gg) {
+        const SegmentPanels sp = segment_panels(tb, gran, gg);
+        if (gg < g) { long_before += sp.has_long; reg_before += sp.nreg; short_before += sp.has_short; }
+        n_long += sp.has_long; n_reg += sp.nreg; n_short += sp.has_short;
+    }
+    const SegmentPanels me = segment_panels(tb, gran, g);
+    reg0 = n_long + reg_before;
+    nreg = me.nreg;
+    extra = me.has_long ? long_before : me.has_short ? n_long + n_reg + short_before : -1;
+}
+
 __device__ __forceinline__ int segment_of_row(const AdapterTable& tb, int row) {
     int g = 0;
     while (g + 1 < tb.G && row >= tb.row0[g + 1]) ++g;

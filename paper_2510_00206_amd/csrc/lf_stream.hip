@@ -48,7 +48,7 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     const int tile = blockIdx.x / p.chunks;
     const int chunk_id = (int)((blockIdx.x - tile * p.chunks + tile) % p.chunks);
     RowTile rt;
-    if (!find_row_tile(p.tb, kRowTile, tile, rt)) return;
+    if (!find_panel(p.tb, kRowTile, tile, rt)) return;
     const int c0 = chunk_id * kStreamChunk;
     const int cols_valid = min(kStreamChunk, p.C - c0);       // multiple of 64
     const int t = threadIdx.x, l = t & 63, w = t >> 6;
@@ -263,17 +263,11 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     }
 }
 
-static int count_tiles(const AdapterTable& tb, int gran) {
-    int n = 0;
-    for (int g = 0; g < tb.G; ++g) n += (tb.row0[g + 1] - tb.row0[g] + gran - 1) / gran;
-    return n;
-}
-
 template <int CB, bool IS_DA>
 static hipError_t launch_stream_t(StreamArgs a, hipStream_t st) {
     constexpr int R = CB * 16;
     const int lds = ST_BIG_BYTES + ST_STEP * R * 2 + (IS_DA ? 0 : kStreamChunk * R * 2 + 4 * CB * 64 * 16);
-    a.tiles_m = count_tiles(a.tb, kRowTile);
+    a.tiles_m = count_panels(a.tb, kRowTile);
     a.chunks = (a.C + kStreamChunk - 1) / kStreamChunk;
     if (a.tiles_m == 0) return hipSuccess;
     hipError_t e = hipFuncSetAttribute((const void*)stream_kernel<CB, IS_DA>,
@@ -326,13 +320,13 @@ __global__ void __launch_bounds__(256) finalize_ds_db_kernel(FinalizeArgs p, int
         if (idx >= per_g * p.tb.G) return;
         const int g = (int)(idx / per_g);
         const int64_t e = idx - g * per_g;
-        int tile0 = 0;
-        for (int gg = 0; gg < g; ++gg) tile0 += (p.tb.row0[gg + 1] - p.tb.row0[gg] + kRowTile - 1) / kRowTile;
-        const int nt = (p.tb.row0[g + 1] - p.tb.row0[g] + kRowTile - 1) / kRowTile;
-        if (nt == 0 && p.accumulate) return;
+        int reg0, nreg, extra;
+        segment_planes(p.tb, kRowTile, g, reg0, nreg, extra);
+        if (nreg == 0 && extra < 0 && p.accumulate) return;
         f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
-        for (int tl = tile0; tl < tile0 + nt; ++tl) v += *(const f32x4*)(p.part_db + ((int64_t)tl * per_g + e) * 4);
+        for (int tl = reg0; tl < reg0 + nreg; ++tl) v += *(const f32x4*)(p.part_db + ((int64_t)tl * per_g + e) * 4);
+        if (extra >= 0) v += *(const f32x4*)(p.part_db + ((int64_t)extra * per_g + e) * 4);
         f32x4* out = (f32x4*)(p.dB + idx * 4);
         *out = p.accumulate ? *out + v : v;
     }
@@ -345,13 +339,13 @@ __global__ void __launch_bounds__(256) finalize_da_kernel(FinalizeArgs p) {
     if (idx >= per_g * p.tb.G) return;
     const int g = (int)(idx / per_g);
     const int64_t e = idx - g * per_g;
-    int tile0 = 0;
-    for (int gg = 0; gg < g; ++gg) tile0 += (p.tb.row0[gg + 1] - p.tb.row0[gg] + kRowTile - 1) / kRowTile;
-    const int nt = (p.tb.row0[g + 1] - p.tb.row0[g] + kRowTile - 1) / kRowTile;
-    if (nt == 0 && p.accumulate) return;
+    int reg0, nreg, extra;
+    segment_planes(p.tb, kRowTile, g, reg0, nreg, extra);
+    if (nreg == 0 && extra < 0 && p.accumulate) return;
     f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
-    for (int tl = tile0; tl < tile0 + nt; ++tl) v += *(const f32x4*)(p.part_da + ((int64_t)tl * per_g + e) * 4);
+    for (int tl = reg0; tl < reg0 + nreg; ++tl) v += *(const f32x4*)(p.part_da + ((int64_t)tl * per_g + e) * 4);
+    if (extra >= 0) v += *(const f32x4*)(p.part_da + ((int64_t)extra * per_g + e) * 4);
     f32x4* out = (f32x4*)(p.dA + idx * 4);
     *out = p.accumulate ? *out + v : v;
 }
