@@ -68,12 +68,13 @@ template <typename F>
 hipError_t timed(int id, hipStream_t st, F&& launch) {
     if (!g_prof_on) return launch();
     ProfRec r{nullptr, nullptr, id};
-    if (hipEventCreate(&r.beg) != hipSuccess || hipEventCreate(&r.end) != hipSuccess) return hipErrorUnknown;
-    hipEventRecord(r.beg, st);
-    hipError_t e = launch();
-    hipEventRecord(r.end, st);
+    if (hipEventCreate(&r.beg) != hipSuccess) return hipErrorUnknown;
+    if (hipEventCreate(&r.end) != hipSuccess) { (void)hipEventDestroy(r.beg); return hipErrorUnknown; }
+    hipError_t e = hipEventRecord(r.beg, st);
+    if (e == hipSuccess) e = launch();
+    const hipError_t e2 = hipEventRecord(r.end, st);
     g_prof.push_back(r);
-    return e;
+    return e != hipSuccess ? e : e2;
 }
 
 struct Workspace {
@@ -237,7 +238,7 @@ const char* lora_status_string(lora_status st) {
 int lora_version(void) { return 100; }
 
 lora_status lora_profile_begin(void) {
-    for (ProfRec& r : g_prof) { hipEventDestroy(r.beg); hipEventDestroy(r.end); }
+    for (ProfRec& r : g_prof) { (void)hipEventDestroy(r.beg); (void)hipEventDestroy(r.end); }
     g_prof.clear();
     g_prof_on = true;
     return LORA_OK;
@@ -253,8 +254,8 @@ lora_status lora_profile_end(float* ms_total, int32_t* launches) {
         if (hipEventSynchronize(r.end) != hipSuccess || hipEventElapsedTime(&ms, r.beg, r.end) != hipSuccess)
             st = LORA_ERR_HIP;
         else if (r.id >= 0 && r.id < LORA_PROF_KERNELS) { ms_total[r.id] += ms; launches[r.id] += 1; }
-        hipEventDestroy(r.beg);
-        hipEventDestroy(r.end);
+        (void)hipEventDestroy(r.beg);
+        (void)hipEventDestroy(r.end);
     }
     g_prof.clear();
     return st;

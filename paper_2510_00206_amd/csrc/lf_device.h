@@ -127,11 +127,11 @@ __device__ __forceinline__ bool find_panel(const AdapterTable& tb, int gran, int
 // Plane indices of segment g's panels: regular planes [reg0, reg0 + nreg), then `extra` (its long or
 // short panel, -1 if none).  The finalize kernels add them in exactly this order.
 __device__ __forceinline__ void segment_planes(const AdapterTable& tb, int gran, int g, int& reg0, int& nreg, int& extra) {
-    int n_long = 0, n_reg = 0, n_short = 0, long_before = 0, reg_before = 0, short_before = 0;
+    int n_long = 0, n_reg = 0, long_before = 0, reg_before = 0, short_before = 0;
     for (int gg = 0; gg < tb.G; ++gg) {
         const SegmentPanels sp = segment_panels(tb, gran, gg);
         if (gg < g) { long_before += sp.has_long; reg_before += sp.nreg; short_before += sp.has_short; }
-        n_long += sp.has_long; n_reg += sp.nreg; n_short += sp.has_short;
+        n_long += sp.has_long; n_reg += sp.nreg;
     }
     const SegmentPanels me = segment_panels(tb, gran, g);
     reg0 = n_long + reg_before;

@@ -1,15 +1,17 @@
 // The two compute-bound kernels of the fused LoRA linear layer (Section 5.1, FusedLoRA Design):
 //   operation (2)  Y  = X W + S' B          (base GEMM with the up-projection folded in)
-//   operation (5)  dX = dY W^T + mask*q*(dS A^T)   (base gradient GEMM + masked LoRA gradient)
+//   operation (5)  dX = dY W^T + mask*q*(dS A^T)   (base gradient GEMM + masked LoRA gradient; dS arrives
+//                                                  already scaled by s*q)
 // with storage layouts X [M,K], W [N,K], S' [M,r], B [N,r], dY [M,N], dS [M,r], A [r,K].
 //
 // Both run a 256x256 output tile per workgroup: 4 waves, one per SIMD, each owning 128x128 of the
 // tile as 4x4 MFMA 32x32x16 bf16 blocks (256 fp32 accumulator registers; sixteen independent
 // accumulator chains per wave is what keeps the matrix pipe full on this chip).  64-deep operand
 // slabs are copied global -> LDS without passing through registers, double-buffered, and the
-// rank-r LoRA term rides as extra contraction steps on the same accumulators.  (2) contracts over the contiguous dimension of both operands; (5) contracts over
-// the row dimension of W (and of A), which it reads from LDS with transposing loads so that no
-// transposed copy of the frozen weight is ever kept.
+// rank-r LoRA term rides as extra contraction steps on the same accumulators.  (2) contracts over
+// the contiguous dimension of both operands; (5) contracts over the row dimension of W (and of A),
+// which it reads from LDS with transposing loads so that no transposed copy of the frozen weight is
+// ever kept.
 #include "lf_device.h"
 #include "lf_internal.h"
 
@@ -234,20 +236,6 @@ __device__ __forceinline__ void slab_step(f32x16 (&acc)[4][4], Frags& f0, Frags&
     wait_slab_loads();
     __syncthreads();
     phase_slots<OUT_IS_COL_SLAB, 0, 0, 0, 8, 16, 2>(acc, f1, f0, nxt_tok, nxt_out, fl, nx);
-}
-
-// A slab with a run-time number of sub-steps (the rank-r LoRA slab: r/16 sub-steps), as one rolled
-// loop so that the accumulators stay in place.
-template <bool OUT_IS_COL_SLAB>
-__device__ __forceinline__ void mma_slab_rolled(f32x16 (&acc)[4][4], const char* lds_tok, const char* lds_out,
-                                                const FragLanes& fl, int nkk) {
-    const int l = threadIdx.x & 63;
-#pragma unroll 1
-    for (int kk = 0; kk < nkk; ++kk) {
-        Frags f;
-        read_frags<OUT_IS_COL_SLAB>(f, lds_tok, lds_out, fl, row_slab_off(l & 31, 2 * kk + (l >> 5)), kk * 8192);
-        mma_frags<0, 4>(acc, f);
-    }
 }
 
 // Accumulator element (mi, ni, i) of lane l is output row  wm*128 + mi*32 + (l & 31)  and output

@@ -22,7 +22,7 @@ struct FwdGemmArgs {
     const lora_bf16* X; const lora_bf16* W; const lora_bf16* S; const lora_bf16* B; lora_bf16* Y;
     int M, K, N, r, tiles_m, tiles_n;
     AdapterTable tb;
-    int uniform_tiles;         // set by the launcher: 256-row tiles over the packed batch (boundaries % 64 == 0)
+    int uniform_tiles = 0;     // set by the launcher: 256-row tiles over the packed batch (boundaries % 64 == 0)
 };
 
 // Operations (3) and (4) share one streaming kernel (see lf_stream.hip).
@@ -51,7 +51,7 @@ struct DxGemmArgs {
     const lora_bf16* dY; const lora_bf16* W; const lora_bf16* dS; const lora_bf16* A; lora_bf16* dX;
     int M, K, N, r, tiles_m, tiles_n;
     AdapterTable tb;
-    int uniform_tiles;
+    int uniform_tiles = 0;
 };
 
 constexpr int kRowTile = 256;        // row-tile granularity of the GEMMs and of the dA/dB partials

@@ -14,7 +14,6 @@ namespace lf {
 
 constexpr int ST_THREADS = 512;
 constexpr int ST_STEP = 64;                        // rows per step
-constexpr int ST_CH16 = kStreamChunk / 8;          // 16-byte chunks per panel row: 64
 constexpr int ST_BIG_BYTES = ST_STEP * kStreamChunk * 2;   // 64 KB
 
 #define LF_MFMA16(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_bf16((a), (b), (c), 0, 0, 0)
