@@ -73,3 +73,15 @@ def test_host_side_validation_needs_no_gpu(lib):
     assert b(ok_ptr, ok_ptr, ok_ptr, ok_ptr, ok_ptr, ok_ptr, 256, 128, 128, 16, 1.0, 0.1, 1,
              ok_ptr, ok_ptr, ok_ptr, 0, None, need, None) == 1
     assert lib.lora_debug_mask(4, 4, 1.5, 1, ok_ptr, None) == 4
+    # per-adapter ranks: each 16, 32 or 64 and at most the allocated rank
+    offs = (C.c_int64 * 3)(0, 64, 128)
+    mr = lib.multi_lora_fwd_ranked
+    for bad in ((16, 48), (64, 16), (0, 16)):
+        ranks = (C.c_int32 * 2)(*bad)
+        assert mr(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 128, 64, 64, 32, 2, offs, ranks, s, p, sd, ok_ptr, ok_ptr, None) == 7
+    ranks = (C.c_int32 * 2)(16, 32)
+    assert mr(None, ok_ptr, ok_ptr, ok_ptr, 128, 64, 64, 32, 2, offs, ranks, s, p, sd, ok_ptr, ok_ptr, None) == 1
+    need = lib.lora_bwd_workspace_bytes(128, 64, 64, 32, 2)
+    mb = lib.multi_lora_bwd_ranked
+    assert mb(ok_ptr, ok_ptr, ok_ptr, ok_ptr, ok_ptr, ok_ptr, 128, 64, 64, 32, 2, offs, ranks, s, p, sd,
+              ok_ptr, ok_ptr, ok_ptr, 0, C.c_void_p(0x100000), need - 1, None) == 6
