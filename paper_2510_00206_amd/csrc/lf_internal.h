@@ -35,6 +35,7 @@ struct StreamArgs {
     int M, C, r;               // C = N for (3), K for (4)
     int tiles_m, chunks;
     AdapterTable tb;
+    int panel_rows = 0;        // set by the launcher: rows per panel (stream_panel_rows)
 };
 
 // Reductions of the partials.
@@ -44,6 +45,7 @@ struct FinalizeArgs {
     const float* part_da; float* dA;            // dA[g,c,j] (+)= q_g * sum over the row tiles of segment g
     int M, K, N, r, chunks, accumulate;
     AdapterTable tb;
+    int panel_rows_db = 0, panel_rows_da = 0;   // set by the launchers: the panel heights operations (3) / (4) ran with
 };
 
 // Operation (5).
@@ -56,6 +58,17 @@ struct DxGemmArgs {
 
 constexpr int kRowTile = 256;        // row-tile granularity of the GEMMs and of the dA/dB partials
 constexpr int kStreamChunk = 512;    // column-chunk width of the streaming kernel
+
+// Rows per panel of a streaming reduction over a [M, C] activation.  Every panel leaves an fp32 partial
+// of C x r (dB) or r x C (dA) values, so taller panels mean less partial traffic; the height is raised
+// from 256 as long as the launch still has about one workgroup per compute unit.  Used by the launcher
+// of the streaming kernel and by the finalize launchers (same inputs, same answer).
+inline int stream_panel_rows(const AdapterTable& tb, int C) {
+    const int chunks = (C + kStreamChunk - 1) / kStreamChunk;
+    for (int rows = 4 * kRowTile; rows > kRowTile; rows >>= 1)
+        if (count_panels(tb, rows) * chunks >= 224) return rows;
+    return kRowTile;
+}
 
 hipError_t launch_down(const DownArgs& a, hipStream_t st);
 hipError_t launch_fwd_gemm(FwdGemmArgs a, hipStream_t st);

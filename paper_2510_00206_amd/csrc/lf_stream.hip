@@ -47,7 +47,7 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     const int tile = blockIdx.x / p.chunks;
     const int chunk_id = (int)((blockIdx.x - tile * p.chunks + tile) % p.chunks);
     RowTile rt;
-    if (!find_panel(p.tb, kRowTile, tile, rt)) return;
+    if (!find_panel(p.tb, p.panel_rows, tile, rt)) return;
     const int c0 = chunk_id * kStreamChunk;
     const int cols_valid = min(kStreamChunk, p.C - c0);       // multiple of 64
     const int t = threadIdx.x, l = t & 63, w = t >> 6;
@@ -78,18 +78,19 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     // last row, columns past the end read the last valid chunk): with predicated loads the compiler cannot
     // count what is in flight and waits for all of it - also the loads of the step after - before a step's
     // data is used.  What the clamped lanes bring is multiplied by zero rows of the small operand (rows)
-    // or never stored (columns).
+    // or never stored (columns).  For the same reason the loops below load two steps past the end of the
+    // panel (all lanes then read the panel's last row, which is cache resident) and, for an odd number
+    // of steps, run one empty step.
     const int bchunk_ld = min(bchunk, (cols_valid >> 3) - 1);
     auto load_step = [&](StepRegs& rg, int step) {
-        const int rows_left = rt.rows - step * ST_STEP;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int row = min((t >> 6) + 8 * i, rows_left - 1);
-            rg.b[i] = *(const u32x4*)(big + (int64_t)(step * ST_STEP + row) * p.C + bchunk_ld * 8);
+            const int row = min(step * ST_STEP + (t >> 6) + 8 * i, rt.rows - 1);     // row of the panel
+            rg.b[i] = *(const u32x4*)(big + (int64_t)row * p.C + bchunk_ld * 8);
         }
         const int ts = min(t, ST_STEP * RCH - 1);
         const int row = ts / RCH, ch = ts - row * RCH;
-        rg.s = *(const u32x4*)(small_ + (int64_t)(step * ST_STEP + min(row, rows_left - 1)) * R + ch * 8);
+        rg.s = *(const u32x4*)(small_ + (int64_t)min(step * ST_STEP + row, rt.rows - 1) * R + ch * 8);
     };
     auto store_step = [&](const StepRegs& rg, int step) {
 #pragma unroll
@@ -188,57 +189,32 @@ __global__ void __launch_bounds__(ST_THREADS, 1) stream_kernel(StreamArgs p) {
     constexpr bool TWO_AHEAD = !(CB == 4 && !IS_DA);
     if constexpr (TWO_AHEAD) {
         StepRegs ra, rb2;
-        if (nsteps == 4) {
-            // full 256-row tile, written out as straight-line code: with the loads behind run-time
-            // conditions the compiler merges the in-flight counts of both paths and waits for everything
-            // before a step's data is used, which shortens the prefetch distance to one step
-            // (the scheduling barriers keep the loads where they are written: the scheduler otherwise
-            // sinks them towards their use)
-            load_step(ra, 0);
-            load_step(rb2, 1);
-            __builtin_amdgcn_sched_barrier(0);
-            stage_b_chunk();                           // after the first panel loads are in flight
-            store_step(ra, 0);
-            __syncthreads();
-            load_step(ra, 2);
-            __builtin_amdgcn_sched_barrier(0);
-            compute_step(0);
-            store_step(rb2, 1);
-            __syncthreads();
-            load_step(rb2, 3);
-            __builtin_amdgcn_sched_barrier(0);
-            compute_step(1);
-            store_step(ra, 2);
-            __syncthreads();
-            compute_step(2);
-            store_step(rb2, 3);
-            __syncthreads();
-            compute_step(3);
-        } else {
         load_step(ra, 0);
-        if (nsteps > 1) load_step(rb2, 1);
+        load_step(rb2, 1);
+        __builtin_amdgcn_sched_barrier(0);             // (the scheduler otherwise sinks loads towards their use)
         stage_b_chunk();                               // after the first panel loads are in flight
         for (int step = 0; step < nsteps; step += 2) {
             store_step(ra, step);
             __syncthreads();
-            if (step + 2 < nsteps) load_step(ra, step + 2);
+            load_step(ra, step + 2);
+            __builtin_amdgcn_sched_barrier(0);
             compute_step(step);
-            if (step + 1 < nsteps) {
-                store_step(rb2, step + 1);
-                __syncthreads();
-                if (step + 3 < nsteps) load_step(rb2, step + 3);
-                compute_step(step + 1);
-            }
-        }
+            store_step(rb2, step + 1);
+            __syncthreads();
+            load_step(rb2, step + 3);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_step(step + 1);
         }
     } else {
         StepRegs ra;
         load_step(ra, 0);
+        __builtin_amdgcn_sched_barrier(0);
         stage_b_chunk();
         for (int step = 0; step < nsteps; ++step) {
             store_step(ra, step);
             __syncthreads();
-            if (step + 1 < nsteps) load_step(ra, step + 1);
+            load_step(ra, step + 1);
+            __builtin_amdgcn_sched_barrier(0);
             compute_step(step);
         }
     }
@@ -266,7 +242,8 @@ template <int CB, bool IS_DA>
 static hipError_t launch_stream_t(StreamArgs a, hipStream_t st) {
     constexpr int R = CB * 16;
     const int lds = ST_BIG_BYTES + ST_STEP * R * 2 + (IS_DA ? 0 : kStreamChunk * R * 2 + 4 * CB * 64 * 16);
-    a.tiles_m = count_panels(a.tb, kRowTile);
+    a.panel_rows = stream_panel_rows(a.tb, a.C);
+    a.tiles_m = count_panels(a.tb, a.panel_rows);
     a.chunks = (a.C + kStreamChunk - 1) / kStreamChunk;
     if (a.tiles_m == 0) return hipSuccess;
     hipError_t e = hipFuncSetAttribute((const void*)stream_kernel<CB, IS_DA>,
@@ -320,7 +297,7 @@ __global__ void __launch_bounds__(256) finalize_ds_db_kernel(FinalizeArgs p, int
         const int g = (int)(idx / per_g);
         const int64_t e = idx - g * per_g;
         int reg0, nreg, extra;
-        segment_planes(p.tb, kRowTile, g, reg0, nreg, extra);
+        segment_planes(p.tb, p.panel_rows_db, g, reg0, nreg, extra);
         if (nreg == 0 && extra < 0 && p.accumulate) return;
         f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
@@ -339,7 +316,7 @@ __global__ void __launch_bounds__(256) finalize_da_kernel(FinalizeArgs p) {
     const int g = (int)(idx / per_g);
     const int64_t e = idx - g * per_g;
     int reg0, nreg, extra;
-    segment_planes(p.tb, kRowTile, g, reg0, nreg, extra);
+    segment_planes(p.tb, p.panel_rows_da, g, reg0, nreg, extra);
     if (nreg == 0 && extra < 0 && p.accumulate) return;
     f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
@@ -354,13 +331,17 @@ hipError_t launch_finalize_ds_db(const FinalizeArgs& a, hipStream_t st) {
     const int64_t n_db = a.part_db ? (int64_t)a.tb.G * a.N * (a.r >> 2) : 0;
     if (n_ds + n_db == 0) return hipSuccess;
     const int blocks_ds = (int)((n_ds + 255) / 256), blocks_db = (int)((n_db + 255) / 256);
-    hipLaunchKernelGGL(finalize_ds_db_kernel, dim3(blocks_ds + blocks_db), dim3(256), 0, st, a, blocks_ds);
+    FinalizeArgs b = a;
+    b.panel_rows_db = stream_panel_rows(a.tb, a.N);
+    hipLaunchKernelGGL(finalize_ds_db_kernel, dim3(blocks_ds + blocks_db), dim3(256), 0, st, b, blocks_ds);
     return hipGetLastError();
 }
 
 hipError_t launch_finalize_da(const FinalizeArgs& a, hipStream_t st) {
     const int64_t n = (int64_t)a.tb.G * a.r * (a.K >> 2);
-    hipLaunchKernelGGL(finalize_da_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+    FinalizeArgs b = a;
+    b.panel_rows_da = stream_panel_rows(a.tb, a.K);
+    hipLaunchKernelGGL(finalize_da_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, b);
     return hipGetLastError();
 }
 
