@@ -1,0 +1,50 @@
+"""Seeded random configurations (valid inputs only): segment counts and lengths (on and off the 64-row
+grid, empty segments), widths, ranks (also per adapter), scales and dropout rates drawn at random; every
+segment is compared with the oracle run on that segment alone."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2510_00206_amd import binding, workloads
+from gpu_util import TOL, f64, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_configurations(seed):
+    rng = np.random.default_rng(seed)
+    for case in range(8):
+        G = int(rng.integers(1, 6))
+        on64 = rng.random() < 0.5
+        lens = [int(rng.integers(0, 9)) * 64 if on64 else int(rng.integers(0, 600)) for _ in range(G)]
+        if sum(lens) == 0:
+            lens[0] = 64
+        M = sum(lens)
+        K, N = int(rng.integers(1, 9)) * 64, int(rng.integers(1, 9)) * 64
+        r = int(rng.choice([16, 32, 64]))
+        ranks = [int(rng.choice([x for x in (16, 32, 64) if x <= r])) for _ in range(G)] if rng.random() < 0.5 else None
+        L = workloads.custom_layer(M, K, N, r, 1.0, 0.1, seg_lens=lens, cfg=20 + case)
+        X, W, A, B, dY = workloads.make_inputs(L)
+        s = [float(rng.uniform(0.25, 3)) for _ in range(G)]
+        p = [float(rng.choice([0.0, 0.05, 0.1, 0.5, 0.9])) for _ in range(G)]
+        seeds = [int(rng.integers(0, 2 ** 63)) for _ in range(G)]
+        print(f"seed {seed} case {case}: M={M} K={K} N={N} r={r} lens={lens} ranks={ranks} p={p}", flush=True)
+        Xg, Wg, Ag, Bg, dYg = (t.cuda() for t in (X, W, A, B, dY))
+        Y, S = binding.multi_lora_fwd(Xg, Wg, Ag, Bg, L.seg_offsets, s, p, seeds, ranks=ranks)
+        dX, dA, dB = binding.multi_lora_bwd(Xg, Wg, Ag, Bg, S, dYg, L.seg_offsets, s, p, seeds, ranks=ranks)
+        torch.cuda.synchronize()
+        o = L.seg_offsets
+        for g in range(G):
+            if o[g + 1] == o[g]:
+                assert not dA[g].any() and not dB[g].any()
+                continue
+            sl, rg = slice(o[g], o[g + 1]), (ranks[g] if ranks else r)
+            Yr, Sr = oracle.lora_fwd(f64(X[sl]), f64(W), f64(A[g, :rg]), f64(B[g, :, :rg]), s[g], p[g], seeds[g])
+            dXr, dAr, dBr, _ = oracle.lora_bwd(f64(X[sl]), f64(W), f64(A[g, :rg]), f64(B[g, :, :rg]), f64(dY[sl]),
+                                               s[g], p[g], seeds[g])
+            errs = dict(Y=rel_err(Y[sl], Yr), dX=rel_err(dX[sl], dXr), dA=rel_err(dA[g, :rg], dAr),
+                        dB=rel_err(dB[g, :, :rg], dBr), S=rel_err(S[sl, :rg], Sr * float(np.float32(s[g]))))
+            assert max(errs.values()) <= TOL, (seed, case, g, errs)
+            assert not S[sl, rg:].any() and not dA[g, rg:].any() and not dB[g, :, rg:].any()
