@@ -97,6 +97,8 @@ def main():
                     help="time the unfused multi-kernel baseline instead of the fused path (comparison runs)")
     ap.add_argument("--sweep", action="store_true",
                     help="token-count x rank sweep at K=N=4096: fused LoRA, unfused baseline and frozen linear (one JSON line each)")
+    ap.add_argument("--row-tile", type=int, default=0, choices=(0, 128, 256),
+                    help="token rows per GEMM tile: 0 lets every launch choose (default), 128 or 256 fixes it (comparison runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 1 GiB device copy 10 times (reference reading for HBM byte counters)")
     args = ap.parse_args()
@@ -112,6 +114,7 @@ def main():
     binding.load_library()                     # fails loudly if the HIP library is not built
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    binding.lora_set_gemm_row_tile(args.row_tile)
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)

@@ -132,6 +132,14 @@ lora_status multi_lora_bwd_ranked(const lora_bf16* X, const lora_bf16* W, const 
 lora_status lora_debug_mask(int64_t M, int64_t K, float p, uint64_t seed, uint8_t* keep,
                             lora_stream stream);
 
+/* Tuning knob and test hook (process-wide, not thread safe).  The two GEMM kernels (operations (2)
+ * and (5), Section 5.1) exist with 256 and with 128 token rows per output tile; by default every launch
+ * picks the tile that needs fewer rounds of workgroups over the chip (the small one for short batches
+ * and narrow projections).  rows = 128 or 256 fixes the tile for all later calls, rows = 0 restores
+ * the automatic choice; any other value returns LORA_ERR_PARAM.  Results do not depend on the tile
+ * beyond fp32 summation order in the LoRA term of mixed-adapter tiles. */
+lora_status lora_set_gemm_row_tile(int32_t rows);
+
 /* Diagnostic per-kernel timing for benchmarks.  Between lora_profile_begin() and
  * lora_profile_end() every kernel the entry points above enqueue is bracketed by a pair of HIP
  * events on the caller's stream (the events are created by the library: do not use inside graph

@@ -237,6 +237,12 @@ const char* lora_status_string(lora_status st) {
 
 int lora_version(void) { return 100; }
 
+lora_status lora_set_gemm_row_tile(int32_t rows) {
+    if (rows != 0 && rows != 128 && rows != 256) return LORA_ERR_PARAM;
+    force_gemm_row_tile(rows);
+    return LORA_OK;
+}
+
 lora_status lora_profile_begin(void) {
     for (ProfRec& r : g_prof) { (void)hipEventDestroy(r.beg); (void)hipEventDestroy(r.end); }
     g_prof.clear();

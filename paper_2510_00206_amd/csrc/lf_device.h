@@ -158,7 +158,7 @@ __device__ __forceinline__ void find_uniform_tile(const AdapterTable& tb, int M,
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int row = rt.row_start + 64 * q;
-        gm.g[q] = (q == 0 || row < M) ? segment_of_row(tb, row) : gm.g[q - 1];
+        gm.g[q] = (q == 0 || (64 * q < gran && row < M)) ? segment_of_row(tb, row) : gm.g[q - 1];
         if (q > 0 && gm.g[q] != gm.g[0]) gm.mixed = true;
     }
     rt.g = gm.g[0];

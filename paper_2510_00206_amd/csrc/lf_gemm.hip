@@ -6,7 +6,9 @@
 //
 // Both run a 256x256 output tile per workgroup: 4 waves, one per SIMD, each owning 128x128 of the
 // tile as 4x4 MFMA 32x32x16 bf16 blocks (256 fp32 accumulator registers; sixteen independent
-// accumulator chains per wave is what keeps the matrix pipe full on this chip).  64-deep operand
+// accumulator chains per wave is what keeps the matrix pipe full on this chip).  A second
+// instantiation with 128 token rows per tile (2x4 blocks per wave) serves problems whose 256-row
+// tiling would leave compute units without a tile.  64-deep operand
 // slabs are copied global -> LDS without passing through registers, double-buffered, and the
 // rank-r LoRA term rides as extra contraction steps on the same accumulators.  (2) contracts over
 // the contiguous dimension of both operands; (5) contracts over the row dimension of W (and of A),
@@ -17,10 +19,10 @@
 
 namespace lf {
 
-constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int BN = 256, BK = 64;            // token rows per tile: 64 * MB (MB = 32-row blocks per wave: 4 or 2)
 constexpr int NTHREADS = 256;
 constexpr int NWAVES = NTHREADS / 64;
-constexpr int TILE_BYTES = BM * BK * 2;            // one 256x64 (or 64x256) bf16 slab: 32 KB
+constexpr int TILE_BYTES = BN * BK * 2;            // one 256x64 (or 64x256) bf16 slab: 32 KB (a 128-row token slab uses half)
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;        // both operands
 constexpr int GEMM_LDS_BYTES = 2 * STAGE_BYTES;    // double buffered: 128 KB
 
@@ -91,11 +93,13 @@ __device__ __forceinline__ SlabLanes col_slab_lanes(int64_t ld, int rows_valid, 
     return s;
 }
 
-// Enqueue one slab: `src` is the (workgroup-uniform) address of the slab's first element.
+// Enqueue one slab (its first NP wave-passes: a 128-row token slab has 4): `src` is the
+// (workgroup-uniform) address of the slab's first element.
+template <int NP = PASSES>
 __device__ __forceinline__ void load_slab(uint32_t lds_slab_addr, const lora_bf16* src, const SlabLanes& s) {
     const uint32_t wave = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
 #pragma unroll
-    for (int i = 0; i < PASSES; ++i)
+    for (int i = 0; i < NP; ++i)
         copy16_to_lds((const char*)src, s.off[i], lds_slab_addr + i * (NWAVES * 1024) + wave);
 }
 
@@ -123,12 +127,12 @@ __device__ __forceinline__ FragLanes frag_lanes() {
     return f;
 }
 
-struct Frags { bf16x8 fo[4], ft[4]; };
+template <int MB> struct Frags { bf16x8 fo[4], ft[MB]; };
 
 // lds_tok / lds_out already include the wave's row (wm*128 rows) and column (wn*128) origin.
 // row_off_kk: fl.row_off[kk]; col_step: kk * 8192.
-template <bool OUT_IS_COL_SLAB>
-__device__ __forceinline__ void read_frags(Frags& f, const char* lds_tok, const char* lds_out,
+template <bool OUT_IS_COL_SLAB, int MB>
+__device__ __forceinline__ void read_frags(Frags<MB>& f, const char* lds_tok, const char* lds_out,
                                            const FragLanes& fl, int row_off_kk, int col_step) {
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
@@ -141,20 +145,20 @@ __device__ __forceinline__ void read_frags(Frags& f, const char* lds_tok, const 
         }
     }
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+    for (int mi = 0; mi < MB; ++mi)
         f.ft[mi] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_tok + row_off_kk + mi * 4096));
 }
 
-// MFMAs of token-row blocks [MI0, MI1) against all four output-column blocks.
-template <int MI0, int MI1>
-__device__ __forceinline__ void mma_frags(f32x16 (&acc)[4][4], const Frags& f) {
+// MFMAs of all token-row blocks against all four output-column blocks.
+template <int MB>
+__device__ __forceinline__ void mma_frags(f32x16 (&acc)[MB][4], const Frags<MB>& f) {
 #pragma unroll
-    for (int mi = MI0; mi < MI1; ++mi)
+    for (int mi = 0; mi < MB; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = LF_MFMA(f.fo[ni], f.ft[mi], acc[mi][ni]);
 }
 
-// What the next slab pair is copied from: two operand slabs of PASSES wave-passes each.
+// What the next slab pair is copied from: a token slab of 2*MB wave-passes and an out slab of PASSES.
 struct NextSlabs {
     const char* src_tok; const char* src_out;     // workgroup-uniform addresses of the slabs' first elements
     const SlabLanes& lanes_tok; const SlabLanes& lanes_out;
@@ -162,19 +166,20 @@ struct NextSlabs {
     bool valid;
 };
 
-// Copy number J (0 .. 2*PASSES-1) of the next slab pair.
-template <int J>
+// Copy number J (0 .. 2*MB+PASSES-1) of the next slab pair.
+template <int MB, int J>
 __device__ __forceinline__ void issue_copy(const NextSlabs& nx) {
     if (!nx.valid) return;
-    if (J < PASSES) copy16_to_lds(nx.src_tok, nx.lanes_tok.off[J], nx.lds_tok + J * (NWAVES * 1024));
-    else copy16_to_lds(nx.src_out, nx.lanes_out.off[J - PASSES], nx.lds_out + (J - PASSES) * (NWAVES * 1024));
+    constexpr int TOKP = 2 * MB;
+    if (J < TOKP) copy16_to_lds(nx.src_tok, nx.lanes_tok.off[J], nx.lds_tok + J * (NWAVES * 1024));
+    else copy16_to_lds(nx.src_out, nx.lanes_out.off[J - TOKP], nx.lds_out + (J - TOKP) * (NWAVES * 1024));
 }
 
 // One operand fragment read of the next sub-step.  Items come in the order the MFMAs need them
 // (MFMA slot s uses out fragment s & 3 and token fragment s >> 2): out0, tok0, out1, out2, out3,
-// tok1, tok2, tok3.
-template <bool OUT_IS_COL_SLAB, int ITEM>
-__device__ __forceinline__ void read_frag_item(Frags& f, const char* lds_tok, const char* lds_out,
+// tok1, tok2, tok3 (MB + 4 items).
+template <bool OUT_IS_COL_SLAB, int MB, int ITEM>
+__device__ __forceinline__ void read_frag_item(Frags<MB>& f, const char* lds_tok, const char* lds_out,
                                                const FragLanes& fl, int row_off_kk, int col_step) {
     constexpr bool is_tok = ITEM == 1 || ITEM >= 5;
     constexpr int i = ITEM == 0 ? 0 : ITEM == 1 ? 0 : ITEM <= 4 ? ITEM - 1 : ITEM - 4;
@@ -189,27 +194,39 @@ __device__ __forceinline__ void read_frag_item(Frags& f, const char* lds_tok, co
     }
 }
 
-// One sub-step: 16 MFMAs, each followed by at most one other instruction group - on even slots a
-// fragment read of the next sub-step, on odd slots a global->LDS copy of the next slab pair - so that
+// One sub-step: 4*MB MFMAs, each followed by at most one other instruction group (two in the 128-row
+// variant) - fragment reads of the next sub-step and global->LDS copies of the next slab pair - so that
 // every LDS read and every copy is issued while an MFMA executes (a copy or read issued between two
-// groups of MFMAs leaves the matrix pipe idle for its whole issue time).
+// groups of MFMAs leaves the matrix pipe idle for its whole issue time).  With MB = 4 reads sit on
+// even slots and copies on odd ones; with MB = 2 the six reads sit on slots 0..5 and copies on odd slots.
 // MODE 0: reads of sub-step KK_NEXT + copies; MODE 1: MFMAs only; MODE 2: reads of the next slab's sub-step 0.
-template <bool OUT_IS_COL_SLAB, int KK_NEXT, int COPY0, int COPIES, int SLOT0, int SLOT1, int MODE>
-__device__ __forceinline__ void phase_slots(f32x16 (&acc)[4][4], const Frags& cur, Frags& nxt, const char* lds_tok,
-                                            const char* lds_out, const FragLanes& fl, const NextSlabs& nx) {
+template <bool OUT_IS_COL_SLAB, int MB, int KK_NEXT, int COPY0, int COPIES, int SLOT0, int SLOT1, int MODE>
+__device__ __forceinline__ void phase_slots(f32x16 (&acc)[MB][4], const Frags<MB>& cur, Frags<MB>& nxt,
+                                            const char* lds_tok, const char* lds_out, const FragLanes& fl,
+                                            const NextSlabs& nx) {
 #define LF_SLOT(S)                                                                                        \
-    if constexpr ((S) >= SLOT0 && (S) < SLOT1) {                                                         \
+    if constexpr ((S) >= SLOT0 && (S) < SLOT1 && (S) < 4 * MB) {                                         \
         acc[(S) >> 2][(S) & 3] = LF_MFMA(cur.fo[(S) & 3], cur.ft[(S) >> 2], acc[(S) >> 2][(S) & 3]);      \
         if constexpr (MODE == 2) {                                                                        \
-            /* hand-over half: all eight fragment reads of the next slab ride on slots 8..15 */         \
-            if (nx.valid)                                                                                 \
-                read_frag_item<OUT_IS_COL_SLAB, ((S) - 8)>(nxt, lds_tok, lds_out, fl, fl.row_off[0], 0);    \
+            /* hand-over half: all fragment reads of the next slab ride on the last 2*MB slots */       \
+            if (nx.valid) {                                                                               \
+                read_frag_item<OUT_IS_COL_SLAB, MB, ((S) - 2 * MB)>(nxt, lds_tok, lds_out, fl, fl.row_off[0], 0); \
+                if constexpr (MB == 2 && (S) < 6)                                                         \
+                    read_frag_item<OUT_IS_COL_SLAB, MB, (S)>(nxt, lds_tok, lds_out, fl, fl.row_off[0], 0);  \
+            }                                                                                             \
         } else if constexpr (MODE == 1) {                                                                 \
-        } else if constexpr (((S) & 1) == 0) {                                                            \
-            read_frag_item<OUT_IS_COL_SLAB, ((S) >> 1)>(nxt, lds_tok, lds_out, fl, fl.row_off[KK_NEXT],     \
-                                                       KK_NEXT * 8192);                                  \
-        } else if constexpr (((S) >> 1) < COPIES) {                                                       \
-            issue_copy<(COPY0 + ((S) >> 1))>(nx);                                                           \
+        } else if constexpr (MB == 4) {                                                                   \
+            if constexpr (((S) & 1) == 0)                                                                 \
+                read_frag_item<OUT_IS_COL_SLAB, MB, ((S) >> 1)>(nxt, lds_tok, lds_out, fl, fl.row_off[KK_NEXT], \
+                                                               KK_NEXT * 8192);                          \
+            else if constexpr (((S) >> 1) < COPIES)                                                       \
+                issue_copy<MB, (COPY0 + ((S) >> 1))>(nx);                                                   \
+        } else {                                                                                          \
+            if constexpr ((S) < MB + 4)                                                                   \
+                read_frag_item<OUT_IS_COL_SLAB, MB, (S)>(nxt, lds_tok, lds_out, fl, fl.row_off[KK_NEXT],   \
+                                                        KK_NEXT * 8192);                                 \
+            if constexpr (((S) & 1) == 1 && ((S) >> 1) < COPIES)                                          \
+                issue_copy<MB, (COPY0 + ((S) >> 1))>(nx);                                                   \
         }                                                                                                 \
         __builtin_amdgcn_sched_barrier(0);                                                                \
     }
@@ -218,41 +235,49 @@ __device__ __forceinline__ void phase_slots(f32x16 (&acc)[4][4], const Frags& cu
 #undef LF_SLOT
 }
 
-// One 64-deep slab pair: sub-steps 0..3, the 16 copies of the next slab pair spread over sub-steps
-// 0 and 1, and in the middle of sub-step 3 the hand-over (copies landed, workgroup barrier) followed by
-// the first fragment reads of the next slab.  On entry f0 holds the fragments of sub-step 0 of the
-// current slab; on exit it holds those of the next slab.
-template <bool OUT_IS_COL_SLAB>
-__device__ __forceinline__ void slab_step(f32x16 (&acc)[4][4], Frags& f0, Frags& f1, const char* cur_tok,
+// One 64-deep slab pair: sub-steps 0..3, the copies of the next slab pair (16 spread over sub-steps
+// 0 and 1; 12 over sub-steps 0..2 in the 128-row variant), and in the middle of sub-step 3 the hand-over
+// (copies landed, workgroup barrier) followed by the first fragment reads of the next slab.  On entry
+// f0 holds the fragments of sub-step 0 of the current slab; on exit it holds those of the next slab.
+template <bool OUT_IS_COL_SLAB, int MB>
+__device__ __forceinline__ void slab_step(f32x16 (&acc)[MB][4], Frags<MB>& f0, Frags<MB>& f1, const char* cur_tok,
                                           const char* cur_out, const char* nxt_tok, const char* nxt_out,
                                           const FragLanes& fl, const NextSlabs& nx) {
-    static_assert(PASSES == 8, "copy schedule below assumes 16 copies per slab pair");
+    static_assert(PASSES == 8 && (MB == 4 || MB == 2), "copy schedule below assumes 8 + 2*MB copies per slab pair");
+    constexpr int NS = 4 * MB;
     __builtin_amdgcn_sched_barrier(0);
-    phase_slots<OUT_IS_COL_SLAB, 1, 0, 8, 0, 16, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx);   // copies 0..7
-    phase_slots<OUT_IS_COL_SLAB, 2, 8, 8, 0, 16, 0>(acc, f1, f0, cur_tok, cur_out, fl, nx);   // copies 8..15
-    phase_slots<OUT_IS_COL_SLAB, 3, 0, 0, 0, 16, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx);
+    if constexpr (MB == 4) {
+        phase_slots<OUT_IS_COL_SLAB, MB, 1, 0, 8, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx);   // copies 0..7
+        phase_slots<OUT_IS_COL_SLAB, MB, 2, 8, 8, 0, NS, 0>(acc, f1, f0, cur_tok, cur_out, fl, nx);   // copies 8..15
+        phase_slots<OUT_IS_COL_SLAB, MB, 3, 0, 0, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx);
+    } else {
+        phase_slots<OUT_IS_COL_SLAB, MB, 1, 0, 4, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx);   // copies 0..3
+        phase_slots<OUT_IS_COL_SLAB, MB, 2, 4, 4, 0, NS, 0>(acc, f1, f0, cur_tok, cur_out, fl, nx);   // copies 4..7
+        phase_slots<OUT_IS_COL_SLAB, MB, 3, 8, 4, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx);   // copies 8..11
+    }
     // sub-step 3: first half, hand-over, second half with the next slab's first fragment reads
-    phase_slots<OUT_IS_COL_SLAB, 0, 0, 0, 0, 8, 1>(acc, f1, f0, cur_tok, cur_out, fl, nx);
+    phase_slots<OUT_IS_COL_SLAB, MB, 0, 0, 0, 0, NS / 2, 1>(acc, f1, f0, cur_tok, cur_out, fl, nx);
     wait_slab_loads();
     __syncthreads();
-    phase_slots<OUT_IS_COL_SLAB, 0, 0, 0, 8, 16, 2>(acc, f1, f0, nxt_tok, nxt_out, fl, nx);
+    phase_slots<OUT_IS_COL_SLAB, MB, 0, 0, 0, NS / 2, NS, 2>(acc, f1, f0, nxt_tok, nxt_out, fl, nx);
 }
 
-// Accumulator element (mi, ni, i) of lane l is output row  wm*128 + mi*32 + (l & 31)  and output
+// Accumulator element (mi, ni, i) of lane l is output row  wm*32*MB + mi*32 + (l & 31)  and output
 // column  wn*128 + ni*32 + 8*(i >> 2) + 4*(l >> 5) + (i & 3)  of the tile: a lane owns groups of four
 // consecutive columns of one row.  Storing those 8-byte groups directly would touch 32 different
-// rows per instruction; instead each wave transposes its 128x128 bf16 sub-tile through its own 32 KB
+// rows per instruction; instead each wave transposes its (32*MB)x128 bf16 sub-tile through its own 32 KB
 // of the (now idle) slab LDS and writes whole 256-byte row segments, 16 bytes per lane.
-// LDS layout per wave: 128 rows x 32 eight-byte slots, slot index XOR-ed with (row & 31) so that the
+// LDS layout per wave: 32*MB rows x 32 eight-byte slots, slot index XOR-ed with (row & 31) so that the
 // 32 rows written by one instruction land in 32 different slots.
-__device__ __forceinline__ void store_tile(const f32x16 (&acc)[4][4], lora_bf16* out, int64_t ld,
+template <int MB>
+__device__ __forceinline__ void store_tile(const f32x16 (&acc)[MB][4], lora_bf16* out, int64_t ld,
                                            int row_start, int rows_valid, int col_start, int cols_valid,
                                            int wm, int wn, char* smem) {
     const int l = threadIdx.x & 63;
     __syncthreads();                                   // every wave is done reading operand slabs
     char* reg = smem + (threadIdx.x >> 6) * 32768;
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
+    for (int mi = 0; mi < MB; ++mi) {
         const int r = mi * 32 + (l & 31);
 #pragma unroll
         for (int ni = 0; ni < 4; ++ni)
@@ -270,11 +295,11 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[4][4], lora_bf16*
     const int j = l & 15;                              // 16-byte chunk of the row: columns 8j .. 8j+7
     const bool col_ok = wn * 128 + j * 8 < cols_valid;
 #pragma unroll 8
-    for (int it = 0; it < 32; ++it) {
+    for (int it = 0; it < 8 * MB; ++it) {
         const int r = it * 4 + (l >> 4);
         u32x4 v = *(const u32x4*)(reg + r * 256 + ((j ^ ((r & 31) >> 1)) << 4));
         if (r & 1) v = u32x4{v.z, v.w, v.x, v.y};      // odd rows hold the two slots of a chunk swapped
-        const int row = wm * 128 + r;
+        const int row = wm * (32 * MB) + r;
         if (col_ok && row < rows_valid)
             // write-once output: a non-temporal store keeps it from displacing the operands (and the
             // activations that the next kernels re-read) in the L2 and the memory-side cache
@@ -282,17 +307,18 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[4][4], lora_bf16*
     }
 }
 
-__device__ __forceinline__ void zero_acc(f32x16 (&acc)[4][4]) {
+template <int MB>
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[MB][4]) {
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+    for (int mi = 0; mi < MB; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 4; ++ni)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
-    // pin the 256 register writes here (callers place them between the issue of the first slab copies
+    // pin the register writes here (callers place them between the issue of the first slab copies
     // and the wait for them); otherwise they are sunk to the first use, after the wait
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+    for (int mi = 0; mi < MB; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 4; ++ni) asm volatile("" : "+a"(acc[mi][ni]));
 }
@@ -310,6 +336,7 @@ __device__ __forceinline__ int group_adapter(const GroupMap& gm, int q) {
 // add exactly S'_i . B_g(i) (the other blocks contribute exact zeros).  runs * r <= 128 contraction
 // columns fit: chunks 0..7 of each row go to stage `lo`, chunks 8..15 to the other stage.  Written
 // with ordinary stores (zeros cannot come from a global->LDS copy); returns the number of sub-steps.
+template <int MB>
 __device__ __forceinline__ int build_mixed_lora_slabs(char* smem, int lo, const lora_bf16* S_tile,
                                                       const lora_bf16* B, int N, int n0, int r, int rows_valid,
                                                       int cols_valid, const GroupMap& gm, const AdapterTable& tb) {
@@ -335,7 +362,7 @@ __device__ __forceinline__ int build_mixed_lora_slabs(char* smem, int lo, const 
     const int rc_shift = rc == 2 ? 1 : rc == 4 ? 2 : 3;
     __syncthreads();                                     // every wave is done with both stages
 #pragma unroll 1
-    for (int idx = threadIdx.x; idx < BM * 16; idx += NTHREADS) {
+    for (int idx = threadIdx.x; idx < BN * 16; idx += NTHREADS) {   // row: token row (< 64*MB) and out column
         const int row = idx >> 4, cc = idx & 15;
         const int j = cc >> rc_shift, sub = cc & (rc - 1);
         const int q = row >> 6;
@@ -344,11 +371,11 @@ __device__ __forceinline__ int build_mixed_lora_slabs(char* smem, int lo, const 
         const int rank_j = j == 0 ? rank_of_run[0] : j == 1 ? rank_of_run[1] : j == 2 ? rank_of_run[2] : rank_of_run[3];
         u32x4 tv = {0u, 0u, 0u, 0u}, bv = {0u, 0u, 0u, 0u};
         if (j < nruns && sub * 8 < rank_j) {             // columns past the adapter's own rank stay zero
-            if (rq == j) tv = *(const u32x4*)(S_tile + (int64_t)min(row, rows_valid - 1) * r + sub * 8);
+            if (rq == j && row < 64 * MB) tv = *(const u32x4*)(S_tile + (int64_t)min(row, rows_valid - 1) * r + sub * 8);
             bv = *(const u32x4*)(B + ((int64_t)gj * N + n0 + min(row, cols_valid - 1)) * r + sub * 8);
         }
         char* dst = smem + ((cc & 8) ? STAGE_BYTES - lo : lo) + row_slab_off(row, cc & 7);
-        *(u32x4*)dst = tv;
+        if (row < 64 * MB) *(u32x4*)dst = tv;
         *(u32x4*)(dst + TILE_BYTES) = bv;
     }
     __syncthreads();
@@ -356,7 +383,9 @@ __device__ __forceinline__ int build_mixed_lora_slabs(char* smem, int lo, const 
 }
 
 // ---- operation (2): Y = X W + S' B ---------------------------------------------------------------
+template <int MB>
 __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
+    constexpr int BM = 64 * MB;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int tm, tn;
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
@@ -376,12 +405,12 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     const lora_bf16* Xt = p.X + (int64_t)rt.row_start * p.K;
     const lora_bf16* Wt = p.W + (int64_t)n0 * p.K;
 
-    f32x16 acc[4][4];
+    f32x16 acc[MB][4];
 
     const int nk = p.K / BK;
     const uint32_t lds0 = lds_addr_of(smem);
     const FragLanes fl = frag_lanes();
-    const int tok_org = wm * 128 * 128, out_org = TILE_BYTES + wn * 128 * 128;
+    const int tok_org = wm * (32 * MB) * 128, out_org = TILE_BYTES + wn * 128 * 128;
     // p.r == 0 (no LoRA slab) and p.K == 0 (LoRA slab only) serve the unfused baseline's plain GEMMs.
     const bool has_lora = p.r > 0;
     const int rr = has_lora ? p.r : 16;
@@ -390,23 +419,23 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     const lora_bf16* Ssrc = p.S + (int64_t)rt.row_start * p.r;
     const lora_bf16* Bsrc = p.B + ((int64_t)rt.g * p.N + n0) * p.r;
     if (nk > 0) {
-        load_slab(lds0, Xt, sx);
+        load_slab<2 * MB>(lds0, Xt, sx);
         load_slab(lds0 + TILE_BYTES, Wt, sw);
     } else {
-        load_slab(lds0, Ssrc, ss);
+        load_slab<2 * MB>(lds0, Ssrc, ss);
         load_slab(lds0 + TILE_BYTES, Bsrc, sb);
     }
     zero_acc(acc);                                     // while the first slabs are on their way
     wait_slab_loads();
     __syncthreads();
-    Frags f0, f1;
+    Frags<MB> f0, f1;
     read_frags<false>(f0, smem + tok_org, smem + out_org, fl, fl.row_off[0], 0);
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
     for (int kt = 0; kt + 1 < nk; ++kt) {
         const int cur = (kt & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
         const NextSlabs nx{(const char*)(Xt + (kt + 1) * BK), (const char*)(Wt + (kt + 1) * BK), sx, sw,
                            lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, true};
-        slab_step<false>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
+        slab_step<false, MB>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
                          smem + nxt + out_org, fl, nx);
     }
     if (nk > 0) {
@@ -415,7 +444,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
         const int cur = ((nk - 1) & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
         const NextSlabs nx{(const char*)Ssrc, (const char*)Bsrc, ss, sb,
                            lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, has_lora && !gm.mixed};
-        slab_step<false>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
+        slab_step<false, MB>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
                          smem + nxt + out_org, fl, nx);
     }
     if (has_lora) {
@@ -423,26 +452,28 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
         int nkk = p.tb.rank[rt.g] >> 4;
         if (gm.mixed) {
             // a tile with several adapters: both stages are rebuilt as one wide LoRA slab pair (below)
-            nkk = build_mixed_lora_slabs(smem, lo, Ssrc, p.B, p.N, n0, p.r, rt.rows, cols_valid, gm, p.tb);
+            nkk = build_mixed_lora_slabs<MB>(smem, lo, Ssrc, p.B, p.N, n0, p.r, rt.rows, cols_valid, gm, p.tb);
             read_frags<false>(f0, smem + lo + tok_org, smem + lo + out_org, fl, fl.row_off[0], 0);
         }
-        mma_frags<0, 4>(acc, f0);
+        mma_frags(acc, f0);
         const int l = threadIdx.x & 63;
 #pragma unroll 1
         for (int kk = 1; kk < nkk; ++kk) {
             // sub-steps 4..7 (mixed tiles only) live in the other stage
             const int st = (kk & 4) ? STAGE_BYTES - lo : lo;
-            Frags f;
+            Frags<MB> f;
             read_frags<false>(f, smem + st + tok_org, smem + st + out_org, fl,
                               row_slab_off(l & 31, 2 * (kk & 3) + (l >> 5)), 0);
-            mma_frags<0, 4>(acc, f);
+            mma_frags(acc, f);
         }
     }
     store_tile(acc, p.Y, p.N, rt.row_start, rt.rows, n0, cols_valid, wm, wn, smem);
 }
 
 // ---- operation (5): dX = dY W^T + mask*q*(dS A^T) ------------------------------------------------
+template <int MB>
 __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
+    constexpr int BM = 64 * MB;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int tm, tn;
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
@@ -459,13 +490,13 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     const int cols_valid = min(BN, p.K - j0);
     const int w = threadIdx.x >> 6, wm = w & 1, wn = w >> 1;
 
-    f32x16 acc[4][4];
+    f32x16 acc[MB][4];
 
     const lora_bf16* dYt = p.dY + (int64_t)rt.row_start * p.N;
     const lora_bf16* Wt = p.W + j0;
     const uint32_t lds0 = lds_addr_of(smem);
     const FragLanes fl = frag_lanes();
-    const int tok_org = wm * 128 * 128, out_org = TILE_BYTES + wn * 128 * 2;
+    const int tok_org = wm * (32 * MB) * 128, out_org = TILE_BYTES + wn * 128 * 2;
     const SlabLanes sd = row_slab_lanes(p.N, rt.rows, 8), sw = col_slab_lanes(p.K, BK, cols_valid);
 
     // LoRA step first: acc = dS A^T (dS arrives scaled by s*q), then the mask is applied to the accumulators and the
@@ -475,11 +506,11 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     const SlabLanes ss = row_slab_lanes(p.r > 0 ? p.r : 16, rt.rows, p.r > 0 ? p.r >> 3 : 2);
     const SlabLanes sa = col_slab_lanes(p.K, p.r > 0 ? p.r : 16, cols_valid);
     if (p.r > 0) {
-        load_slab(lds0 + STAGE_BYTES, p.dS + (int64_t)rt.row_start * p.r, ss);
+        load_slab<2 * MB>(lds0 + STAGE_BYTES, p.dS + (int64_t)rt.row_start * p.r, ss);
         load_slab(lds0 + STAGE_BYTES + TILE_BYTES, p.A + (int64_t)gm.g[0] * p.r * p.K + j0, sa);
     }
     if (nk > 0) {
-        load_slab(lds0, dYt + 0, sd);
+        load_slab<2 * MB>(lds0, dYt + 0, sd);
         load_slab(lds0 + TILE_BYTES, Wt, sw);
     }
     zero_acc(acc);                                     // while the first slabs are on their way
@@ -509,9 +540,9 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
             const uint32_t k0 = p.tb.k0[g], k1 = p.tb.k1[g];
             const int lrow0 = rt.row_start - p.tb.row0[g];        // tile row -> row inside the adapter's segment
 #pragma unroll
-            for (int mi = 0; mi < 4; ++mi) {
-                const int row = wm * 128 + mi * 32 + (l & 31);
-                if (wm * 128 + mi * 32 < 64 * q || wm * 128 + mi * 32 >= 64 * qe) continue;
+            for (int mi = 0; mi < MB; ++mi) {
+                const int row = wm * (32 * MB) + mi * 32 + (l & 31);
+                if (wm * (32 * MB) + mi * 32 < 64 * q || wm * (32 * MB) + mi * 32 >= 64 * qe) continue;
                 const RowKey rk = row_key(k0, k1, (uint32_t)(lrow0 + row));
                 const uint32_t x0 = rk.a + cp0 * kGold;
 #pragma unroll
@@ -546,14 +577,14 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
         }
     }
     __syncthreads();                                  // every wave is done with the LoRA slab in stage 1
-    Frags f0, f1;
+    Frags<MB> f0, f1;
     if (nk > 0) read_frags<true>(f0, smem + tok_org, smem + out_org, fl, fl.row_off[0], 0);
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = (kt & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
         const NextSlabs nx{(const char*)(dYt + (kt + 1) * BK), (const char*)(Wt + (int64_t)(kt + 1) * BK * p.K), sd, sw,
                            lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, kt + 1 < nk};
-        slab_step<true>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
+        slab_step<true, MB>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
                         smem + nxt + out_org, fl, nx);
     }
     store_tile(acc, p.dX, p.K, rt.row_start, rt.rows, j0, cols_valid, wm, wn, smem);
@@ -569,11 +600,11 @@ static bool boundaries_on_64(const AdapterTable& tb) {
 }
 
 // Largest number of adapter runs (maximal sequences of 64-row groups with one adapter) in any uniform tile.
-static int max_runs_per_tile(const AdapterTable& tb, int M) {
+static int max_runs_per_tile(const AdapterTable& tb, int M, int bm) {
     int worst = 1;
-    for (int t0 = 0; t0 < M; t0 += BM) {
+    for (int t0 = 0; t0 < M; t0 += bm) {
         int runs = 0, prev = -1;
-        for (int row = t0; row < t0 + BM && row < M; row += 64) {
+        for (int row = t0; row < t0 + bm && row < M; row += 64) {
             int g = 0;
             while (g + 1 < tb.G && row >= tb.row0[g + 1]) ++g;
             if (g != prev) ++runs;
@@ -590,37 +621,63 @@ static int count_row_tiles(const AdapterTable& tb, int gran) {
     return n;
 }
 
-hipError_t launch_fwd_gemm(FwdGemmArgs a, hipStream_t st) {
-    // a mixed tile's LoRA step holds runs * r contraction columns in the two LDS stages: at most 128
-    a.uniform_tiles = a.tb.G > 1 && boundaries_on_64(a.tb) && max_runs_per_tile(a.tb, a.M) * a.r <= 128;
-    a.tiles_m = a.uniform_tiles ? (a.M + BM - 1) / BM : count_row_tiles(a.tb, BM);
-    a.tiles_n = (a.N + BN - 1) / BN;
-    if (a.tiles_m == 0) return hipSuccess;
-    static bool attr_set = false;
+// Row tiling of one launch: uniform tiles over the packed batch or per-segment tiles, of 256 or 128 rows.
+struct RowTiling { int bm; int uniform; int tiles_m; };
+
+// lora_cols_cap: most LoRA contraction columns a mixed tile may hold (0: no limit).
+static int g_forced_row_tile = 0;      // 0: chosen per launch; 128 or 256: fixed (tuning and tests)
+void force_gemm_row_tile(int rows) { g_forced_row_tile = rows; }
+
+static RowTiling plan_row_tiles(const AdapterTable& tb, int M, int r, int tiles_n, int lora_cols_cap) {
+    RowTiling best{256, 0, 0};
+    double best_cost = 0.0;
+    const bool on64 = tb.G > 1 && boundaries_on_64(tb);
+    for (int bm = 256; bm >= 128; bm >>= 1) {
+        if (g_forced_row_tile != 0 && bm != g_forced_row_tile) continue;
+        RowTiling t{bm, 0, 0};
+        t.uniform = on64 && (lora_cols_cap == 0 || max_runs_per_tile(tb, M, bm) * r <= lora_cols_cap);
+        t.tiles_m = t.uniform ? (M + bm - 1) / bm : count_row_tiles(tb, bm);
+        // rounds of workgroups over the compute units, times the relative duration of one tile (a 128-row
+        // tile does half the work of a 256-row one at a lower rate: the out operand is re-read twice as often)
+        const int64_t wgs = (int64_t)t.tiles_m * tiles_n;
+        const double cost = (double)((wgs + kComputeUnits - 1) / kComputeUnits) * (bm == 256 ? 1.0 : 0.6);
+        if (bm == 256 || g_forced_row_tile != 0 || cost < best_cost) { best = t; best_cost = cost; }
+    }
+    return best;
+}
+
+template <typename K, typename A>
+static hipError_t launch_gemm(K kernel, bool& attr_set, const A& a, hipStream_t st) {
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)fwd_gemm_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(fwd_gemm_kernel, dim3(a.tiles_m * a.tiles_n), dim3(NTHREADS), GEMM_LDS_BYTES, st, a);
+    hipLaunchKernelGGL(kernel, dim3(a.tiles_m * a.tiles_n), dim3(NTHREADS), GEMM_LDS_BYTES, st, a);
     return hipGetLastError();
 }
 
-hipError_t launch_bwd_dx(DxGemmArgs a, hipStream_t st) {
-    a.uniform_tiles = a.tb.G > 1 && boundaries_on_64(a.tb);
-    a.tiles_m = a.uniform_tiles ? (a.M + BM - 1) / BM : count_row_tiles(a.tb, BM);
-    a.tiles_n = (a.K + BN - 1) / BN;
+hipError_t launch_fwd_gemm(FwdGemmArgs a, hipStream_t st) {
+    a.tiles_n = (a.N + BN - 1) / BN;
+    // a mixed tile's LoRA step holds runs * r contraction columns in the two LDS stages: at most 128
+    const RowTiling t = plan_row_tiles(a.tb, a.M, a.r, a.tiles_n, 128);
+    a.uniform_tiles = t.uniform;
+    a.tiles_m = t.tiles_m;
     if (a.tiles_m == 0) return hipSuccess;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)bwd_dx_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(bwd_dx_kernel, dim3(a.tiles_m * a.tiles_n), dim3(NTHREADS), GEMM_LDS_BYTES, st, a);
-    return hipGetLastError();
+    static bool attr_set[2] = {false, false};
+    return t.bm == 256 ? launch_gemm(fwd_gemm_kernel<4>, attr_set[0], a, st)
+                       : launch_gemm(fwd_gemm_kernel<2>, attr_set[1], a, st);
+}
+
+hipError_t launch_bwd_dx(DxGemmArgs a, hipStream_t st) {
+    a.tiles_n = (a.K + BN - 1) / BN;
+    const RowTiling t = plan_row_tiles(a.tb, a.M, a.r, a.tiles_n, 0);
+    a.uniform_tiles = t.uniform;
+    a.tiles_m = t.tiles_m;
+    if (a.tiles_m == 0) return hipSuccess;
+    static bool attr_set[2] = {false, false};
+    return t.bm == 256 ? launch_gemm(bwd_dx_kernel<4>, attr_set[0], a, st)
+                       : launch_gemm(bwd_dx_kernel<2>, attr_set[1], a, st);
 }
 
 }  // namespace lf

@@ -56,7 +56,8 @@ struct DxGemmArgs {
     int uniform_tiles = 0;
 };
 
-constexpr int kRowTile = 256;        // row-tile granularity of the GEMMs and of the dA/dB partials
+constexpr int kRowTile = 256;        // row-tile granularity of the dA/dB partials (and the GEMMs' larger tile)
+constexpr int kComputeUnits = 256;   // of the one chip this library is written for
 constexpr int kStreamChunk = 512;    // column-chunk width of the streaming kernel
 
 // Rows per panel of a streaming reduction over a [M, C] activation.  Every panel leaves an fp32 partial
@@ -77,6 +78,7 @@ hipError_t launch_stream_da(StreamArgs a, hipStream_t st);
 hipError_t launch_finalize_ds_db(const FinalizeArgs& a, hipStream_t st);
 hipError_t launch_finalize_da(const FinalizeArgs& a, hipStream_t st);
 hipError_t launch_bwd_dx(DxGemmArgs a, hipStream_t st);
+void force_gemm_row_tile(int rows);   // 0 (automatic), 128 or 256
 hipError_t launch_debug_mask(int64_t M, int64_t K, uint32_t T, uint32_t k0, uint32_t k1, uint8_t* keep,
                              hipStream_t st);
 

@@ -11,10 +11,15 @@ from gpu_util import TOL, compare, f64, rel_err, run_gpu, run_oracle
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module", autouse=True)
-def _lib():
+@pytest.fixture(scope="module", autouse=True, params=[256, 128], ids=["tile256", "tile128"])
+def _lib(request):
+    """Every test of this module runs with each of the two GEMM row tiles fixed (small shapes would
+    otherwise all take the 128-row one); the automatic choice is what the full-size tests run."""
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     binding.load_library()          # raises if the HIP library is not built: no fallback
+    binding.lora_set_gemm_row_tile(request.param)
+    yield
+    binding.lora_set_gemm_row_tile(0)
 
 
 @pytest.mark.parametrize("M,K,p,seed", [(256, 1024, 0.1, 0x25100206), (37, 130, 0.5, 0), (5, 7, 0.05, 1),

@@ -12,8 +12,16 @@ from gpu_util import TOL, f64, rel_err
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(params=[0, 256], ids=["auto", "tile256"])
+def row_tile(request):
+    """Automatic GEMM row tile (128 rows at these sizes) and the 256-row tile fixed."""
+    binding.lora_set_gemm_row_tile(request.param)
+    yield request.param
+    binding.lora_set_gemm_row_tile(0)
+
+
 @pytest.mark.parametrize("seed", [11, 12, 13])
-def test_random_configurations(seed):
+def test_random_configurations(seed, row_tile):
     rng = np.random.default_rng(seed)
     for case in range(8):
         G = int(rng.integers(1, 6))
@@ -30,7 +38,7 @@ def test_random_configurations(seed):
         s = [float(rng.uniform(0.25, 3)) for _ in range(G)]
         p = [float(rng.choice([0.0, 0.05, 0.1, 0.5, 0.9])) for _ in range(G)]
         seeds = [int(rng.integers(0, 2 ** 63)) for _ in range(G)]
-        print(f"seed {seed} case {case}: M={M} K={K} N={N} r={r} lens={lens} ranks={ranks} p={p}", flush=True)
+        print(f"seed {seed} tile {row_tile} case {case}: M={M} K={K} N={N} r={r} lens={lens} ranks={ranks} p={p}", flush=True)
         Xg, Wg, Ag, Bg, dYg = (t.cuda() for t in (X, W, A, B, dY))
         Y, S = binding.multi_lora_fwd(Xg, Wg, Ag, Bg, L.seg_offsets, s, p, seeds, ranks=ranks)
         dX, dA, dB = binding.multi_lora_bwd(Xg, Wg, Ag, Bg, S, dYg, L.seg_offsets, s, p, seeds, ranks=ranks)
