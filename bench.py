@@ -114,7 +114,7 @@ def main():
     binding.load_library()                     # fails loudly if the HIP library is not built
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    binding.lora_set_gemm_row_tile(args.row_tile)
+    binding.lora_set_row_tile(args.row_tile)
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)

@@ -132,13 +132,16 @@ lora_status multi_lora_bwd_ranked(const lora_bf16* X, const lora_bf16* W, const 
 lora_status lora_debug_mask(int64_t M, int64_t K, float p, uint64_t seed, uint8_t* keep,
                             lora_stream stream);
 
-/* Tuning knob and test hook (process-wide, not thread safe).  The two GEMM kernels (operations (2)
- * and (5), Section 5.1) exist with 256 and with 128 token rows per output tile; by default every launch
- * picks the tile that needs fewer rounds of workgroups over the chip (the small one for short batches
- * and narrow projections).  rows = 128 or 256 fixes the tile for all later calls, rows = 0 restores
- * the automatic choice; any other value returns LORA_ERR_PARAM.  Results do not depend on the tile
- * beyond fp32 summation order in the LoRA term of mixed-adapter tiles. */
-lora_status lora_set_gemm_row_tile(int32_t rows);
+/* Tuning knob and test hook (process-wide, not thread safe).  Several kernels exist in more than
+ * one height: the GEMMs of operations (2) and (5) (Section 5.1) with 256 or 128 token rows per output
+ * tile, the down-projection of operation (1) with 32 or 16 token rows per workgroup, and the streaming
+ * reductions of operations (3) and (4) with row panels of 1024 down to 64 rows.  By default every launch
+ * picks the height that fills the chip better (the small ones for short batches and narrow
+ * projections).  rows = 256 fixes the large height of the first three and panels of at least 256 rows
+ * for all later calls, rows = 128 the small height of the first three, rows = 0 restores the automatic
+ * choice; any other value returns LORA_ERR_PARAM.  Y, S_saved and dX are bit-identical under all three
+ * settings; dA and dB are fp32 sums over the row panels and agree up to the order of those sums. */
+lora_status lora_set_row_tile(int32_t rows);
 
 /* Diagnostic per-kernel timing for benchmarks.  Between lora_profile_begin() and
  * lora_profile_end() every kernel the entry points above enqueue is bracketed by a pair of HIP

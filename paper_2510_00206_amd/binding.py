@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "liblorafusion_hip.so")
 
 EXPORTS = ("lora_fwd", "lora_bwd", "multi_lora_fwd", "multi_lora_bwd", "multi_lora_fwd_ranked",
            "multi_lora_bwd_ranked", "lora_bwd_workspace_bytes",
-           "lora_debug_mask", "lora_status_string", "lora_version", "lora_set_gemm_row_tile",
+           "lora_debug_mask", "lora_status_string", "lora_version", "lora_set_row_tile",
            "lora_unfused_fwd", "lora_unfused_bwd", "lora_unfused_workspace_bytes")
 
 _lib = None
@@ -183,9 +183,9 @@ def lora_debug_mask(M, K, p, seed, device="cuda"):
     return keep
 
 
-def lora_set_gemm_row_tile(rows: int):
-    """0: automatic choice per launch; 128 or 256: fixed token rows per GEMM tile."""
-    _check(load_library().lora_set_gemm_row_tile(int(rows)))
+def lora_set_row_tile(rows: int):
+    """0: automatic choice per launch; 128 / 256: the small / large height of the GEMM tiles and the down-projection workgroups."""
+    _check(load_library().lora_set_row_tile(int(rows)))
 
 
 PROF_KERNELS = ("down", "fwd_gemm", "ds_db", "finalize_ds_db", "da", "finalize_da", "dx_gemm")

@@ -82,7 +82,7 @@ struct Workspace {
 };
 
 Workspace carve(void* base, int64_t M, int64_t K, int64_t N, int32_t r, int32_t G) {
-    const int64_t tiles = M / kRowTile + G;                      // upper bound on row tiles
+    const int64_t tiles = max_stream_panels(M, G);               // upper bound on row panels
     const int64_t chunks = (N + kStreamChunk - 1) / kStreamChunk;
     size_t off = 0;
     Workspace w;
@@ -237,9 +237,9 @@ const char* lora_status_string(lora_status st) {
 
 int lora_version(void) { return 100; }
 
-lora_status lora_set_gemm_row_tile(int32_t rows) {
+lora_status lora_set_row_tile(int32_t rows) {
     if (rows != 0 && rows != 128 && rows != 256) return LORA_ERR_PARAM;
-    force_gemm_row_tile(rows);
+    force_row_tile(rows);
     return LORA_OK;
 }
 

@@ -8,14 +8,18 @@
 
 namespace lf {
 
-constexpr int DOWN_ROWS = 32;      // token rows per workgroup (two 16-row MFMA blocks)
+
 constexpr int DOWN_WAVES = 8;      // waves split the K dimension in 32-column chunks
 
 #define LF_MFMA16(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_bf16((a), (b), (c), 0, 0, 0)
 
-template <int CB>   // CB = r / 16 column blocks of S'
+// CB = r / 16 column blocks of S'; RB = 16-row MFMA blocks per workgroup.  The kernel is bound by the
+// vector ALU work of the mask (about 15 instructions per column pair), so a launch with fewer
+// 32-row workgroups than compute units is cut into 16-row workgroups instead.
+template <int CB, int RB>
 __global__ void __launch_bounds__(DOWN_WAVES * 64) down_kernel(DownArgs p) {
-    __shared__ f32x4 red[DOWN_WAVES][2][CB][64];
+    constexpr int DOWN_ROWS = 16 * RB;
+    __shared__ f32x4 red[DOWN_WAVES][RB][CB][64];
     RowTile rt;
     if (!find_row_tile(p.tb, DOWN_ROWS, blockIdx.x, rt)) return;
     const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -24,35 +28,36 @@ __global__ void __launch_bounds__(DOWN_WAVES * 64) down_kernel(DownArgs p) {
     const lora_bf16* Ag = p.A + (int64_t)g * p.r * p.K;
     const int cbn = p.tb.rank[g] >> 4;                  // 16-column blocks this adapter uses (<= CB)
 
-    const lora_bf16* xrow[2];
-    RowKey rk[2];
+    const lora_bf16* xrow[RB];
+    RowKey rk[RB];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
+    for (int rb = 0; rb < RB; ++rb) {
         const int row = rb * 16 + (l & 15);
         xrow[rb] = p.X + (int64_t)(rt.row_start + min(row, rt.rows - 1)) * p.K;
         rk[rb] = row_key(p.tb.k0[g], p.tb.k1[g], (uint32_t)(rt.local_row0 + row));
     }
-    f32x4 acc[2][CB];
+    f32x4 acc[RB][CB];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int nchunks = p.K >> 5;
     // each wave walks its 32-column chunks (w, w + 8, ...) with loads running DEPTH chunks ahead
     constexpr int DEPTH = CB == 1 ? 4 : 2;
-    struct ChunkRegs { u32x4 x[2], a[CB]; };
+    struct ChunkRegs { u32x4 x[RB], a[CB]; };
     ChunkRegs ring[DEPTH];
-    // Every workgroup starts its sweep over K at a different column (a function of its row-tile index
-    // within the segment, so that single- and multi-adapter calls sum in the same order): workgroups
+    // Every workgroup starts its sweep over K at a different column (a function of its 32-row group
+    // within the segment, so that single- and multi-adapter calls, and both workgroup heights, sum in
+    // the same order): workgroups
     // sweeping in lockstep would all hit the same few L2 channels, the row pitch being a multiple of
     // the channel interleave.
-    const int rot = (int)(((unsigned)(rt.local_row0 / DOWN_ROWS) * 5u) % (unsigned)max(nchunks / DOWN_WAVES, 1)) * DOWN_WAVES;
+    const int rot = (int)(((unsigned)(rt.local_row0 / 32) * 5u) % (unsigned)max(nchunks / DOWN_WAVES, 1)) * DOWN_WAVES;
     auto load = [&](ChunkRegs& c, int kc0) {
         const int kc = (kc0 + rot) % nchunks;
         const int col = kc * 32 + 8 * (l >> 4);
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) c.x[rb] = *(const u32x4*)(xrow[rb] + col);
+        for (int rb = 0; rb < RB; ++rb) c.x[rb] = *(const u32x4*)(xrow[rb] + col);
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)
             if (CB == 1 || cb < cbn) c.a[cb] = *(const u32x4*)(Ag + (int64_t)(cb * 16 + (l & 15)) * p.K + col);
@@ -61,7 +66,7 @@ __global__ void __launch_bounds__(DOWN_WAVES * 64) down_kernel(DownArgs p) {
         const int kc = (kc0 + rot) % nchunks;
         const uint32_t col = (uint32_t)(kc * 32 + 8 * (l >> 4));
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
+        for (int rb = 0; rb < RB; ++rb) {
             const bf16x8 xf = __builtin_bit_cast(bf16x8, mask8(c.x[rb], rk[rb], col, T));
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
@@ -82,13 +87,13 @@ __global__ void __launch_bounds__(DOWN_WAVES * 64) down_kernel(DownArgs p) {
         }
     }
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) red[w][rb][cb][l] = acc[rb][cb];
     __syncthreads();
     // fixed-order sum over the waves, scale by s*q, round once to bf16
     const float sq = p.tb.s[g] * p.tb.q[g];
-    for (int idx = threadIdx.x; idx < 2 * CB * 64; idx += DOWN_WAVES * 64) {
+    for (int idx = threadIdx.x; idx < RB * CB * 64; idx += DOWN_WAVES * 64) {
         const int lane = idx & 63, cb = (idx >> 6) % CB, rb = (idx >> 6) / CB;
         f32x4 v = red[0][rb][cb][lane];
 #pragma unroll
@@ -103,18 +108,29 @@ __global__ void __launch_bounds__(DOWN_WAVES * 64) down_kernel(DownArgs p) {
     }
 }
 
-hipError_t launch_down(const DownArgs& a, hipStream_t st) {
-    int tiles = 0;
-    for (int g = 0; g < a.tb.G; ++g) tiles += (a.tb.row0[g + 1] - a.tb.row0[g] + DOWN_ROWS - 1) / DOWN_ROWS;
-    if (tiles == 0) return hipSuccess;
+template <int RB>
+static hipError_t launch_down_rows(const DownArgs& a, int tiles, hipStream_t st) {
     const dim3 grid(tiles), block(DOWN_WAVES * 64);
     switch (a.r) {
-        case 16: hipLaunchKernelGGL(down_kernel<1>, grid, block, 0, st, a); break;
-        case 32: hipLaunchKernelGGL(down_kernel<2>, grid, block, 0, st, a); break;
-        case 64: hipLaunchKernelGGL(down_kernel<4>, grid, block, 0, st, a); break;
+        case 16: hipLaunchKernelGGL((down_kernel<1, RB>), grid, block, 0, st, a); break;
+        case 32: hipLaunchKernelGGL((down_kernel<2, RB>), grid, block, 0, st, a); break;
+        case 64: hipLaunchKernelGGL((down_kernel<4, RB>), grid, block, 0, st, a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
+}
+
+hipError_t launch_down(const DownArgs& a, hipStream_t st) {
+    int tiles32 = 0, tiles16 = 0;
+    for (int g = 0; g < a.tb.G; ++g) {
+        const int len = a.tb.row0[g + 1] - a.tb.row0[g];
+        tiles32 += (len + 31) / 32;
+        tiles16 += (len + 15) / 16;
+    }
+    if (tiles32 == 0) return hipSuccess;
+    const int forced = forced_row_tile();
+    const bool small = forced ? forced == 128 : tiles32 < kComputeUnits;
+    return small ? launch_down_rows<1>(a, tiles16, st) : launch_down_rows<2>(a, tiles32, st);
 }
 
 // keep[i,j] for one adapter, one thread per column pair

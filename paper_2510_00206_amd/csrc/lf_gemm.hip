@@ -626,7 +626,8 @@ struct RowTiling { int bm; int uniform; int tiles_m; };
 
 // lora_cols_cap: most LoRA contraction columns a mixed tile may hold (0: no limit).
 static int g_forced_row_tile = 0;      // 0: chosen per launch; 128 or 256: fixed (tuning and tests)
-void force_gemm_row_tile(int rows) { g_forced_row_tile = rows; }
+void force_row_tile(int rows) { g_forced_row_tile = rows; }
+int forced_row_tile() { return g_forced_row_tile; }
 
 static RowTiling plan_row_tiles(const AdapterTable& tb, int M, int r, int tiles_n, int lora_cols_cap) {
     RowTiling best{256, 0, 0};

@@ -60,15 +60,32 @@ constexpr int kRowTile = 256;        // row-tile granularity of the dA/dB partia
 constexpr int kComputeUnits = 256;   // of the one chip this library is written for
 constexpr int kStreamChunk = 512;    // column-chunk width of the streaming kernel
 
+void force_row_tile(int rows);        // 0 (automatic), or the small (128) / large (256) height of every kernel that has two
+int forced_row_tile();
+
 // Rows per panel of a streaming reduction over a [M, C] activation.  Every panel leaves an fp32 partial
-// of C x r (dB) or r x C (dA) values, so taller panels mean less partial traffic; the height is raised
-// from 256 as long as the launch still has about one workgroup per compute unit.  Used by the launcher
-// of the streaming kernel and by the finalize launchers (same inputs, same answer).
+// of C x r (dB) or r x C (dA) values, so taller panels mean less partial traffic, while a launch with
+// fewer workgroups than compute units is bound by the latency of one workgroup's sweep: the height is
+// the largest of 1024 .. 64 that still gives about one workgroup per compute unit (256 at least when
+// the large kernel heights are forced).  Used by the launcher of the streaming kernel and by the
+// finalize launchers (same inputs, same answer).
+constexpr int kStreamFill = 224;     // workgroups that count as "about one per compute unit"
 inline int stream_panel_rows(const AdapterTable& tb, int C) {
     const int chunks = (C + kStreamChunk - 1) / kStreamChunk;
-    for (int rows = 4 * kRowTile; rows > kRowTile; rows >>= 1)
-        if (count_panels(tb, rows) * chunks >= 224) return rows;
-    return kRowTile;
+    const int lowest = forced_row_tile() == 256 ? kRowTile : 64;
+    for (int rows = 4 * kRowTile; rows > lowest; rows >>= 1)
+        if (count_panels(tb, rows) * chunks >= kStreamFill) return rows;
+    return lowest;
+}
+
+// Upper bound on the number of panels (planes of dA / dB partials) of any launch over M rows in G
+// segments.  Height h gives at most M/h + G panels.  A height h < 256 is only chosen when height 2h
+// gives fewer than kStreamFill panels, which needs M/(2h) < kStreamFill + G, i.e. M/h + G < 2 kStreamFill + 3 G.
+inline int64_t max_stream_panels(int64_t M, int G) {
+    const int64_t tall = M / kRowTile + G;
+    int64_t low = M / 64 + G;
+    if (low > 2 * kStreamFill + 3 * G) low = 2 * kStreamFill + 3 * G;
+    return tall > low ? tall : low;
 }
 
 hipError_t launch_down(const DownArgs& a, hipStream_t st);
@@ -78,7 +95,6 @@ hipError_t launch_stream_da(StreamArgs a, hipStream_t st);
 hipError_t launch_finalize_ds_db(const FinalizeArgs& a, hipStream_t st);
 hipError_t launch_finalize_da(const FinalizeArgs& a, hipStream_t st);
 hipError_t launch_bwd_dx(DxGemmArgs a, hipStream_t st);
-void force_gemm_row_tile(int rows);   // 0 (automatic), 128 or 256
 hipError_t launch_debug_mask(int64_t M, int64_t K, uint32_t T, uint32_t k0, uint32_t k1, uint8_t* keep,
                              hipStream_t st);
 

@@ -86,7 +86,7 @@ struct UWorkspace {
 };
 
 UWorkspace carve(void* base, int64_t M, int64_t K, int64_t N, int32_t r) {
-    const int64_t tiles = M / kRowTile + 1, chunks = (N + kStreamChunk - 1) / kStreamChunk;
+    const int64_t tiles = max_stream_panels(M, 1), chunks = (N + kStreamChunk - 1) / kStreamChunk;
     char* b = (char*)base;
     size_t off = 0;
     UWorkspace w;

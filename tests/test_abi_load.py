@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_version_and_status_strings(lib):
     assert lib.lora_version() >= 100
-    assert [lib.lora_set_gemm_row_tile(v) for v in (128, 256, 64, -1, 0)] == [0, 0, 4, 4, 0]
+    assert [lib.lora_set_row_tile(v) for v in (128, 256, 64, -1, 0)] == [0, 0, 4, 4, 0]
     assert lib.lora_status_string(0) == b"ok"
     for code in range(1, 9):
         assert len(lib.lora_status_string(code)) > 3

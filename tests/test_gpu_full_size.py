@@ -53,3 +53,10 @@ def test_large_config_parity(cfg, li):
     # the LoRA branch on its own scale is covered by the W = 0 runs above and in test_gpu_parity.py;
     # c3's "up" layer has the shape of "gate"
     _check_layer(workloads.CONFIGS[cfg][li], li)
+
+
+def test_mid_size_parity():
+    """4096 tokens at K = N = 4096 in three segments: the size at which the streaming reductions run
+    128-row panels (256-row ones would leave half the compute units without a workgroup)."""
+    L = workloads.custom_layer(4096, 4096, 4096, 16, 2.0, 0.1, seg_lens=(1536, 2048, 512), cfg=8)
+    _check_layer(L, 0)

@@ -13,13 +13,14 @@ pytestmark = pytest.mark.gpu
 
 @pytest.fixture(scope="module", autouse=True, params=[256, 128], ids=["tile256", "tile128"])
 def _lib(request):
-    """Every test of this module runs with each of the two GEMM row tiles fixed (small shapes would
-    otherwise all take the 128-row one); the automatic choice is what the full-size tests run."""
+    """Every test of this module runs with the large and with the small height of the kernels that
+    have two (GEMM tiles of 256 / 128 rows, down-projection workgroups of 32 / 16 rows) fixed: small
+    shapes would otherwise all take the small one.  The automatic choice is what the full-size tests run."""
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     binding.load_library()          # raises if the HIP library is not built: no fallback
-    binding.lora_set_gemm_row_tile(request.param)
+    binding.lora_set_row_tile(request.param)
     yield
-    binding.lora_set_gemm_row_tile(0)
+    binding.lora_set_row_tile(0)
 
 
 @pytest.mark.parametrize("M,K,p,seed", [(256, 1024, 0.1, 0x25100206), (37, 130, 0.5, 0), (5, 7, 0.05, 1),

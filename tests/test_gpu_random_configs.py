@@ -14,10 +14,10 @@ pytestmark = pytest.mark.gpu
 
 @pytest.fixture(params=[0, 256], ids=["auto", "tile256"])
 def row_tile(request):
-    """Automatic GEMM row tile (128 rows at these sizes) and the 256-row tile fixed."""
-    binding.lora_set_gemm_row_tile(request.param)
+    """Automatic kernel heights (the small ones at these sizes) and the large ones fixed."""
+    binding.lora_set_row_tile(request.param)
     yield request.param
-    binding.lora_set_gemm_row_tile(0)
+    binding.lora_set_row_tile(0)
 
 
 @pytest.mark.parametrize("seed", [11, 12, 13])
@@ -56,3 +56,30 @@ def test_random_configurations(seed, row_tile):
                         dB=rel_err(dB[g, :, :rg], dBr), S=rel_err(S[sl, :rg], Sr * float(np.float32(s[g]))))
             assert max(errs.values()) <= TOL, (seed, case, g, errs)
             assert not S[sl, rg:].any() and not dA[g, rg:].any() and not dB[g, :, rg:].any()
+
+
+@pytest.mark.parametrize("lens,r,ranks", [((300,), 16, None), ((128, 64, 192, 256), 32, None), ((64, 320, 128), 64, (16, 64, 32)),
+                                          ((100, 37, 250), 16, None)])
+def test_kernel_heights_agree(lens, r, ranks):
+    """The small and the large height of the GEMM tiles and of the down-projection workgroups sum in the
+    same order: Y, S' and dX are the same bits whichever is fixed, and under the automatic choice.  dA and
+    dB are fp32 sums over row panels whose height differs too: equal up to the order of those sums."""
+    L = workloads.custom_layer(sum(lens), 320, 448, r, 1.5, 0.1, seg_lens=lens, cfg=31)
+    Xg, Wg, Ag, Bg, dYg = (t.cuda() for t in workloads.make_inputs(L))
+    s, p = [1.0 + 0.5 * g for g in range(L.G)], [0.1 * (g + 1) for g in range(L.G)]
+    outs = []
+    try:
+        for rows in (0, 128, 256):
+            print(f"heights lens={lens} r={r} ranks={ranks} rows={rows}", flush=True)
+            binding.lora_set_row_tile(rows)
+            Y, S = binding.multi_lora_fwd(Xg, Wg, Ag, Bg, L.seg_offsets, s, p, L.seeds, ranks=ranks)
+            dX, dA, dB = binding.multi_lora_bwd(Xg, Wg, Ag, Bg, S, dYg, L.seg_offsets, s, p, L.seeds, ranks=ranks)
+            torch.cuda.synchronize()
+            outs.append((Y, S, dX, dA, dB))
+    finally:
+        binding.lora_set_row_tile(0)
+    for other in outs[1:]:
+        for a, b, name in zip(outs[0], other, ("Y", "S", "dX")):
+            assert torch.equal(a, b), name
+        for a, b, name in zip(outs[0][3:], other[3:], ("dA", "dB")):
+            assert rel_err(a, f64(b)) <= 1e-5, name
