@@ -116,13 +116,14 @@ lora_status bwd_impl(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A,
     FinalizeArgs fin{ws.part_ds, ws.dS, ws.part_db, dB, ws.part_da, dA,
                      (int)M, (int)K, (int)N, r, chunks, accumulate, tb};
     if (timed(LORA_PROF_FIN_DS_DB, st, [&] { return launch_finalize_ds_db(fin, st); }) != hipSuccess) return LORA_ERR_HIP;
-    StreamArgs s4{X, ws.dS, nullptr, ws.part_da, nullptr, (int)M, (int)K, r, 0, 0, tb};
-    if (timed(LORA_PROF_DA, st, [&] { return launch_stream_da(s4, st); }) != hipSuccess) return LORA_ERR_HIP;
-    if (timed(LORA_PROF_FIN_DA, st, [&] { return launch_finalize_da(fin, st); }) != hipSuccess) return LORA_ERR_HIP;
+    // (5) right after (3): it re-reads dY while that pass's copy still sits in the memory-side cache
     if (dX) {
         DxGemmArgs g5{dY, W, ws.dS, A, dX, (int)M, (int)K, (int)N, r, 0, 0, tb};
         if (timed(LORA_PROF_DX_GEMM, st, [&] { return launch_bwd_dx(g5, st); }) != hipSuccess) return LORA_ERR_HIP;
     }
+    StreamArgs s4{X, ws.dS, nullptr, ws.part_da, nullptr, (int)M, (int)K, r, 0, 0, tb};
+    if (timed(LORA_PROF_DA, st, [&] { return launch_stream_da(s4, st); }) != hipSuccess) return LORA_ERR_HIP;
+    if (timed(LORA_PROF_FIN_DA, st, [&] { return launch_finalize_da(fin, st); }) != hipSuccess) return LORA_ERR_HIP;
     return LORA_OK;
 }
 
