@@ -99,6 +99,9 @@ def main():
                     help="token-count x rank sweep at K=N=4096: fused LoRA, unfused baseline and frozen linear (one JSON line each)")
     ap.add_argument("--row-tile", type=int, default=0, choices=(0, 128, 256),
                     help="token rows per GEMM tile: 0 lets every launch choose (default), 128 or 256 fixes it (comparison runs)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record one step (all layers, forward + backward) into a HIP graph and time replays of it: "
+                         "takes the host's launch work out of launch-bound workloads such as c1")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 1 GiB device copy 10 times (reference reading for HBM byte counters)")
     args = ap.parse_args()
@@ -173,6 +176,16 @@ def main():
                                    st["s"], st["p"], L.seeds, dA=st["dA"], dB=st["dB"],
                                    workspace=st["ws"], dX=st["dX"])
 
+    eager_step = step
+    if args.graph:
+        assert len(sets) == 1, "--graph replays one recorded step: use it without --rotate"
+        eager_step()                           # first launches (kernel attributes) outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            eager_step()
+        step = graph.replay
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -211,7 +224,7 @@ def main():
     # per-kernel durations: same steps again with HIP events around every launch (on the launch stream)
     binding.profile_begin()
     for _ in range(args.steps):
-        step()
+        eager_step()
     prof = binding.profile_end()
     kernels_us = {k: (ms / n * 1e3 if n else 0.0) for k, (ms, n) in prof.items()}
     launches = {k: n for k, (ms, n) in prof.items()}
@@ -244,6 +257,7 @@ def main():
             for st in state)},
         "step_ms": step_ms,
         "buffer_sets": len(sets),
+        "launch": "hip graph replay" if args.graph else "eager",
         "tokens_per_s": round(tokens / (ms_per_step * 1e-3), 1),
         "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "algorithmic_hbm_bytes_per_token": round(fused_bytes / tokens, 1),
