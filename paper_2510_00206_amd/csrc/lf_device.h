@@ -146,7 +146,7 @@ __device__ __forceinline__ int segment_of_row(const AdapterTable& tb, int row) {
 }
 
 // Packed tiling for the GEMMs: when every segment boundary is a multiple of 64 rows, the packed
-// batch is cut into uniform 256-row tiles and a tile may hold up to four adapters, one per 64-row
+// batch is cut into uniform tiles of 256 (or 128) rows and a tile may hold up to four (two) adapters, one per 64-row
 // group; only such mixed tiles take the slower per-group LoRA path.
 struct GroupMap { int g[4]; bool mixed; };
 

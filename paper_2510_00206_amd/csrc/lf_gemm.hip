@@ -65,7 +65,8 @@ __device__ __forceinline__ void wait_slab_loads() { asm volatile("s_waitcnt vmcn
 // Per-lane source offsets of one slab (bytes from the slab's first element), one per pass.
 struct SlabLanes { uint32_t off[PASSES]; };
 
-// Row-operand slab: 256 rows x 64 contraction elements, each row 8 chunks of 16 B (128 B).
+// Row-operand slab: 256 rows (128 for the token slab of a 128-row tile) x 64 contraction elements, each row 8
+// chunks of 16 B (128 B).
 // Wave w, pass i fills rows 8*(NWAVES*i + w) .. +7; lane l is (row l >> 3, physical chunk l & 7).
 __device__ __forceinline__ SlabLanes row_slab_lanes(int64_t ld, int rows_valid, int nchunk_valid) {
     const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -591,7 +592,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
 }
 
 // ---- host launchers -------------------------------------------------------------------------------
-// Uniform 256-row tiles over the packed batch are possible when every segment boundary is a multiple
+// Uniform tiles (256 or 128 rows) over the packed batch are possible when every segment boundary is a multiple
 // of 64 rows (a tile then holds at most four adapters, one per 64-row group).
 static bool boundaries_on_64(const AdapterTable& tb) {
     for (int g = 0; g <= tb.G; ++g)

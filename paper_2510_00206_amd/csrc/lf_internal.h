@@ -22,7 +22,7 @@ struct FwdGemmArgs {
     const lora_bf16* X; const lora_bf16* W; const lora_bf16* S; const lora_bf16* B; lora_bf16* Y;
     int M, K, N, r, tiles_m, tiles_n;
     AdapterTable tb;
-    int uniform_tiles = 0;     // set by the launcher: 256-row tiles over the packed batch (boundaries % 64 == 0)
+    int uniform_tiles = 0;     // set by the launcher: uniform tiles over the packed batch (boundaries % 64 == 0)
 };
 
 // Operations (3) and (4) share one streaming kernel (see lf_stream.hip).

@@ -3,7 +3,7 @@
 //   operation (3), big = dY [M,N]:  dS[i,c] = s sum_n dY[i,n] B[n,c]   and   dB[n,c] = sum_i dY[i,n] S'[i,c]
 //                                   (both from a single read of dY)
 //   operation (4), big = X  [M,K]:  dA[c,j] = q sum_i keep(i,j) X[i,j] dS[i,c]   (mask regenerated)
-// A workgroup owns a (256-row tile) x (512-column chunk) panel of `big`, walks it in 64-row steps
+// A workgroup owns a (row panel of 64 .. 1024 rows) x (512-column chunk) panel of `big`, walks it in 64-row steps
 // through LDS and reduces over its rows with 16x16x32 bf16 MFMAs whose row-contracted operand is
 // fetched with transposing LDS reads.  Results are partial sums (dB/dA per row tile, dS per column
 // chunk) that the finalize kernels add in a fixed order, so repeated runs agree bit for bit.

@@ -39,7 +39,7 @@ SHAPES = [  # M, K, N, r, s, p
     (300, 320, 448, 16, 2.0, 0.1),         # ragged row tile, column tiles of 64 and 192
     (777, 576, 832, 32, 0.5, 0.25),        # several row tiles with a ragged tail, r = 32
     (520, 1088, 640, 64, 0.5, 0.1),        # r = 64, more than one column chunk in the streaming kernels
-    (1100, 256, 192, 16, 1.0, 0.9),        # heavy dropout; 1100 rows: three 256-row panels and a long last one
+    (1100, 256, 192, 16, 1.0, 0.9),        # heavy dropout; 1100 rows: regular row panels and a long last one
     (384, 512, 256, 32, 2.0, 0.99999),     # threshold clipped to 65535: one element in 65536 survives, q = 65536
 ]
 
