@@ -143,6 +143,14 @@ lora_status lora_debug_mask(int64_t M, int64_t K, float p, uint64_t seed, uint8_
  * settings; dA and dB are fp32 sums over the row panels and agree up to the order of those sums. */
 lora_status lora_set_row_tile(int32_t rows);
 
+/* Diagnostic (host only, nothing is enqueued): the row-panel height the streaming reductions of operations
+ * (3) / (4) (Section 5.1) would choose for an activation of C columns over these segments under the current
+ * lora_set_row_tile setting, the number of panels that gives (each leaves one fp32 plane of partial dB or dA
+ * in the workspace), and the number of planes lora_bwd_workspace_bytes provides for.  seg_offsets: host,
+ * G+1 entries rising from 0 to M. */
+lora_status lora_debug_stream_panels(int64_t M, int64_t C, int32_t G, const int64_t* seg_offsets,
+                                     int32_t* panel_rows, int64_t* panels, int64_t* panels_bound);
+
 /* Diagnostic per-kernel timing for benchmarks.  Between lora_profile_begin() and
  * lora_profile_end() every kernel the entry points above enqueue is bracketed by a pair of HIP
  * events on the caller's stream (the events are created by the library: do not use inside graph

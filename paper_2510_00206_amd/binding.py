@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "liblorafusion_hip.so")
 
 EXPORTS = ("lora_fwd", "lora_bwd", "multi_lora_fwd", "multi_lora_bwd", "multi_lora_fwd_ranked",
            "multi_lora_bwd_ranked", "lora_bwd_workspace_bytes",
-           "lora_debug_mask", "lora_status_string", "lora_version", "lora_set_row_tile",
+           "lora_debug_mask", "lora_status_string", "lora_version", "lora_set_row_tile", "lora_debug_stream_panels",
            "lora_unfused_fwd", "lora_unfused_bwd", "lora_unfused_workspace_bytes")
 
 _lib = None

@@ -221,6 +221,24 @@ lora_status lora_debug_mask(int64_t M, int64_t K, float p, uint64_t seed, uint8_
     return LORA_OK;
 }
 
+lora_status lora_debug_stream_panels(int64_t M, int64_t C, int32_t G, const int64_t* seg_offsets,
+                                     int32_t* panel_rows, int64_t* panels, int64_t* panels_bound) {
+    if (!seg_offsets || !panel_rows || !panels || !panels_bound) return LORA_ERR_NULL;
+    if (M < 0 || C <= 0 || M >= (1ll << 31) || C >= (1ll << 31) || G < 1) return LORA_ERR_SHAPE;
+    if (G > kMaxAdapters) return LORA_ERR_UNSUPPORTED;
+    AdapterTable tb;
+    memset(&tb, 0, sizeof(tb));
+    tb.G = G;
+    if (seg_offsets[0] != 0 || seg_offsets[G] != M) return LORA_ERR_SEGMENTS;
+    for (int g = 0; g < G; ++g)
+        if (seg_offsets[g + 1] < seg_offsets[g]) return LORA_ERR_SEGMENTS;
+    for (int g = 0; g <= G; ++g) tb.row0[g] = (int)seg_offsets[g];
+    *panel_rows = stream_panel_rows(tb, (int)C);
+    *panels = count_panels(tb, *panel_rows);
+    *panels_bound = max_stream_panels(M, G);
+    return LORA_OK;
+}
+
 const char* lora_status_string(lora_status st) {
     switch (st) {
         case LORA_OK: return "ok";

@@ -86,3 +86,37 @@ def test_host_side_validation_needs_no_gpu(lib):
     mb = lib.multi_lora_bwd_ranked
     assert mb(ok_ptr, ok_ptr, ok_ptr, ok_ptr, ok_ptr, ok_ptr, 128, 64, 64, 32, 2, offs, ranks, s, p, sd,
               ok_ptr, ok_ptr, ok_ptr, 0, C.c_void_p(0x100000), need - 1, None) == 6
+
+
+def test_workspace_holds_every_panel_choice(lib):
+    """Host logic: whatever row-panel height the streaming reductions pick (all three row-tile settings), the
+    number of partial planes stays within what the workspace query provides for."""
+    import random
+    rnd = random.Random(5)
+    f = lib.lora_debug_stream_panels
+    f.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int32),
+                  C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    rows, panels, bound = C.c_int32(), C.c_int64(), C.c_int64()
+    heights = set()
+    try:
+        for it in range(3000):
+            G = rnd.randint(1, 64)
+            mode = it % 4
+            lens = [rnd.randrange(300) if mode == 0 else rnd.randrange(40) * 64 if mode == 1 else rnd.randrange(5000)
+                    if mode == 2 else rnd.choice((0, rnd.randint(1, 130))) for _ in range(G)]
+            if sum(lens) == 0:
+                lens[0] = 1
+            offs = [0]
+            for v in lens:
+                offs.append(offs[-1] + v)
+            arr = (C.c_int64 * (G + 1))(*offs)
+            for setting in (0, 128, 256):
+                assert lib.lora_set_row_tile(setting) == 0
+                for cols in (64, 512, 4096, 14336, 28672):
+                    assert f(offs[-1], cols, G, arr, C.byref(rows), C.byref(panels), C.byref(bound)) == 0
+                    assert rows.value in (64, 128, 256, 512, 1024) and (setting != 256 or rows.value >= 256)
+                    assert 0 < panels.value <= bound.value, (offs, cols, setting, rows.value, panels.value, bound.value)
+                    heights.add(rows.value)
+    finally:
+        lib.lora_set_row_tile(0)
+    assert heights == {64, 128, 256, 512, 1024}
