@@ -60,3 +60,23 @@ def test_mid_size_parity():
     128-row panels (256-row ones would leave half the compute units without a workgroup)."""
     L = workloads.custom_layer(4096, 4096, 4096, 16, 2.0, 0.1, seg_lens=(1536, 2048, 512), cfg=8)
     _check_layer(L, 0)
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_mid_size_random_configurations(seed):
+    """Seeded random mid-size problems (1024 .. 10240 tokens in 1 .. 4 segments on and off the 64-row grid,
+    K and N of 1024 .. 4096, every rank): the sizes at which the launches switch between their kernel
+    heights.  Sampled rows against the oracle, dA / dB / S' in full."""
+    rng = np.random.default_rng(seed)
+    for case in range(5):
+        G = int(rng.integers(1, 5))
+        tot = int(rng.choice([1024, 2048, 3000, 4096, 6000, 8192, 10240]))
+        cuts = sorted(int(v) for v in rng.integers(0, tot + 1, size=G - 1))
+        if rng.random() < 0.5:
+            cuts, tot = [c // 64 * 64 for c in cuts], tot // 64 * 64
+        offs = [0] + cuts + [tot]
+        lens = [offs[i + 1] - offs[i] for i in range(G)]
+        K, N = int(rng.choice([1024, 2048, 4096])), int(rng.choice([1024, 2048, 4096]))
+        r = int(rng.choice([16, 32, 64]))
+        L = workloads.custom_layer(tot, K, N, r, 2.0, float(rng.choice([0.0, 0.1, 0.5])), seg_lens=lens, cfg=50 + case)
+        _check_layer(L, case)
