@@ -84,8 +84,8 @@ def sweep(torch, binding, workloads, dev, args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="c2", help="c1..c5 (default c2, the headline configuration); layer8b, layer70b (decoder-layer "
                          "composites, 7 LoRA linears) and their _qkv variants (q/k/v as one LoRA linear)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
