@@ -32,8 +32,9 @@
  * - Ownership: the caller owns every buffer.  No entry point allocates or frees device
  *   memory, synchronises the device, or touches a stream other than `stream`; work is only
  *   enqueued.  Inputs are never modified.
- * - Supported sizes: M >= 0 (M == 0 is a no-op), K and N positive multiples of 64 and at most
- *   2^22, r in {16, 32, 64}, 1 <= G <= 64, M < 2^31.
+ * - Supported sizes: M >= 0, K and N positive multiples of 64 and at most 2^22, r in {16, 32, 64},
+ *   1 <= G <= 64, M < 2^31.  With M == 0 a forward call enqueues nothing; a backward call still
+ *   defines its outputs: dA and dB are zero-filled (left untouched if accumulate != 0).
  * - Errors: every call returns a lora_status and enqueues nothing unless it returns LORA_OK.
  *   With M == 0 the token-sized arrays (X, Y, S_saved, dY, dX) are empty and may be NULL.
  */

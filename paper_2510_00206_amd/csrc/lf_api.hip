@@ -98,10 +98,11 @@ Workspace carve(void* base, int64_t M, int64_t K, int64_t N, int32_t r, int32_t 
 lora_status fwd_impl(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
                      int64_t M, int64_t K, int64_t N, int32_t r, const AdapterTable& tb,
                      lora_bf16* Y, lora_bf16* S, hipStream_t st) {
+    const int forced = forced_row_tile();              // the knob is read once per call
     DownArgs d{X, A, S, (int)M, (int)K, r, tb};
-    if (timed(LORA_PROF_DOWN, st, [&] { return launch_down(d, st); }) != hipSuccess) return LORA_ERR_HIP;
+    if (timed(LORA_PROF_DOWN, st, [&] { return launch_down(d, forced, st); }) != hipSuccess) return LORA_ERR_HIP;
     FwdGemmArgs f{X, W, S, B, Y, (int)M, (int)K, (int)N, r, 0, 0, tb};
-    if (timed(LORA_PROF_FWD_GEMM, st, [&] { return launch_fwd_gemm(f, st); }) != hipSuccess) return LORA_ERR_HIP;
+    if (timed(LORA_PROF_FWD_GEMM, st, [&] { return launch_fwd_gemm(f, forced, st); }) != hipSuccess) return LORA_ERR_HIP;
     return LORA_OK;
 }
 
@@ -111,17 +112,22 @@ lora_status bwd_impl(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A,
                      void* workspace, hipStream_t st) {
     const Workspace ws = carve(workspace, M, K, N, r, tb.G);
     const int chunks = (int)((N + kStreamChunk - 1) / kStreamChunk);
-    StreamArgs s3{dY, S, B, ws.part_db, ws.part_ds, (int)M, (int)N, r, 0, 0, tb};
+    // The knob is read once per call and the panel heights are chosen here, for the streaming launches
+    // and for the finalize launches that add their partial planes: a change of the knob by another
+    // thread in the middle of this call cannot make the two disagree.
+    const int forced = forced_row_tile();
+    const int rows_db = stream_panel_rows(tb, (int)N, forced), rows_da = stream_panel_rows(tb, (int)K, forced);
+    StreamArgs s3{dY, S, B, ws.part_db, ws.part_ds, (int)M, (int)N, r, 0, 0, tb, rows_db};
     if (timed(LORA_PROF_DS_DB, st, [&] { return launch_stream_dsdb(s3, st); }) != hipSuccess) return LORA_ERR_HIP;
     FinalizeArgs fin{ws.part_ds, ws.dS, ws.part_db, dB, ws.part_da, dA,
-                     (int)M, (int)K, (int)N, r, chunks, accumulate, tb};
+                     (int)M, (int)K, (int)N, r, chunks, accumulate, tb, rows_db, rows_da};
     if (timed(LORA_PROF_FIN_DS_DB, st, [&] { return launch_finalize_ds_db(fin, st); }) != hipSuccess) return LORA_ERR_HIP;
     // (5) right after (3): it re-reads dY while that pass's copy still sits in the memory-side cache
     if (dX) {
         DxGemmArgs g5{dY, W, ws.dS, A, dX, (int)M, (int)K, (int)N, r, 0, 0, tb};
-        if (timed(LORA_PROF_DX_GEMM, st, [&] { return launch_bwd_dx(g5, st); }) != hipSuccess) return LORA_ERR_HIP;
+        if (timed(LORA_PROF_DX_GEMM, st, [&] { return launch_bwd_dx(g5, forced, st); }) != hipSuccess) return LORA_ERR_HIP;
     }
-    StreamArgs s4{X, ws.dS, nullptr, ws.part_da, nullptr, (int)M, (int)K, r, 0, 0, tb};
+    StreamArgs s4{X, ws.dS, nullptr, ws.part_da, nullptr, (int)M, (int)K, r, 0, 0, tb, rows_da};
     if (timed(LORA_PROF_DA, st, [&] { return launch_stream_da(s4, st); }) != hipSuccess) return LORA_ERR_HIP;
     if (timed(LORA_PROF_FIN_DA, st, [&] { return launch_finalize_da(fin, st); }) != hipSuccess) return LORA_ERR_HIP;
     return LORA_OK;
@@ -233,7 +239,7 @@ lora_status lora_debug_stream_panels(int64_t M, int64_t C, int32_t G, const int6
     for (int g = 0; g < G; ++g)
         if (seg_offsets[g + 1] < seg_offsets[g]) return LORA_ERR_SEGMENTS;
     for (int g = 0; g <= G; ++g) tb.row0[g] = (int)seg_offsets[g];
-    *panel_rows = stream_panel_rows(tb, (int)C);
+    *panel_rows = stream_panel_rows(tb, (int)C, forced_row_tile());
     *panels = count_panels(tb, *panel_rows);
     *panels_bound = max_stream_panels(M, G);
     return LORA_OK;

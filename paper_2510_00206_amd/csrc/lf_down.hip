@@ -120,7 +120,7 @@ static hipError_t launch_down_rows(const DownArgs& a, int tiles, hipStream_t st)
     return hipGetLastError();
 }
 
-hipError_t launch_down(const DownArgs& a, hipStream_t st) {
+hipError_t launch_down(const DownArgs& a, int forced, hipStream_t st) {
     int tiles32 = 0, tiles16 = 0;
     for (int g = 0; g < a.tb.G; ++g) {
         const int len = a.tb.row0[g + 1] - a.tb.row0[g];
@@ -128,7 +128,6 @@ hipError_t launch_down(const DownArgs& a, hipStream_t st) {
         tiles16 += (len + 15) / 16;
     }
     if (tiles32 == 0) return hipSuccess;
-    const int forced = forced_row_tile();
     const bool small = forced ? forced == 128 : tiles32 < kComputeUnits;
     return small ? launch_down_rows<1>(a, tiles16, st) : launch_down_rows<2>(a, tiles32, st);
 }

@@ -14,6 +14,8 @@
 // the contiguous dimension of both operands; (5) contracts over the row dimension of W (and of A),
 // which it reads from LDS with transposing loads so that no transposed copy of the frozen weight is
 // ever kept.
+#include <atomic>
+
 #include "lf_device.h"
 #include "lf_internal.h"
 
@@ -55,10 +57,16 @@ __device__ __forceinline__ uint32_t lds_addr_of(const char* p) {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
 }
 
+// M0 is named as clobbered so that the compiler never keeps a value of its own in it across a copy (it
+// defines M0 itself before indirect register indexing, lane selects and its own LDS-DMA builtins).  Clang
+// warns about every reserved register on a clobber list; the clobber is still recorded, hence the pragma.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void copy16_to_lds(const char* uniform_base, uint32_t lane_byte_off, uint32_t lds_wave_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_wave_addr), "v"(lane_byte_off), "s"(uniform_base) : "memory");
+                 :: "s"(lds_wave_addr), "v"(lane_byte_off), "s"(uniform_base) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 __device__ __forceinline__ void wait_slab_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -330,59 +338,6 @@ __device__ __forceinline__ int group_adapter(const GroupMap& gm, int q) {
     return __builtin_amdgcn_readfirstlane(g);
 }
 
-// LoRA step of a tile that holds several adapters (FusedMultiLoRA with tiles cut uniformly over the
-// packed batch).  The runs of 64-row groups that share an adapter become column blocks of one wide
-// contraction: token operand row i carries S'[i, :] in the block of its own run and zeros elsewhere,
-// out operand column n carries B_g[n, :] of run j's adapter in block j, so the ordinary LoRA sub-steps
-// add exactly S'_i . B_g(i) (the other blocks contribute exact zeros).  runs * r <= 128 contraction
-// columns fit: chunks 0..7 of each row go to stage `lo`, chunks 8..15 to the other stage.  Written
-// with ordinary stores (zeros cannot come from a global->LDS copy); returns the number of sub-steps.
-template <int MB>
-__device__ __forceinline__ int build_mixed_lora_slabs(char* smem, int lo, const lora_bf16* S_tile,
-                                                      const lora_bf16* B, int N, int n0, int r, int rows_valid,
-                                                      int cols_valid, const GroupMap& gm, const AdapterTable& tb) {
-    const int nq = (rows_valid + 63) >> 6;
-    int run_of_q[4], g_of_run[4];
-    int nruns = 1;
-    run_of_q[0] = 0;
-    g_of_run[0] = g_of_run[1] = g_of_run[2] = g_of_run[3] = gm.g[0];
-#pragma unroll
-    for (int q = 1; q < 4; ++q) {
-        if (q < nq && gm.g[q] != gm.g[q - 1]) {
-            if (nruns == 1) g_of_run[1] = gm.g[q];
-            else if (nruns == 2) g_of_run[2] = gm.g[q];
-            else g_of_run[3] = gm.g[q];
-            ++nruns;
-        }
-        run_of_q[q] = nruns - 1;
-    }
-    int rank_of_run[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) rank_of_run[j] = tb.rank[g_of_run[j]];
-    const int rc = r >> 3;                               // 16-byte chunks per adapter block: 2, 4 or 8
-    const int rc_shift = rc == 2 ? 1 : rc == 4 ? 2 : 3;
-    __syncthreads();                                     // every wave is done with both stages
-#pragma unroll 1
-    for (int idx = threadIdx.x; idx < BN * 16; idx += NTHREADS) {   // row: token row (< 64*MB) and out column
-        const int row = idx >> 4, cc = idx & 15;
-        const int j = cc >> rc_shift, sub = cc & (rc - 1);
-        const int q = row >> 6;
-        const int rq = q == 0 ? run_of_q[0] : q == 1 ? run_of_q[1] : q == 2 ? run_of_q[2] : run_of_q[3];
-        const int gj = j == 0 ? g_of_run[0] : j == 1 ? g_of_run[1] : j == 2 ? g_of_run[2] : g_of_run[3];
-        const int rank_j = j == 0 ? rank_of_run[0] : j == 1 ? rank_of_run[1] : j == 2 ? rank_of_run[2] : rank_of_run[3];
-        u32x4 tv = {0u, 0u, 0u, 0u}, bv = {0u, 0u, 0u, 0u};
-        if (j < nruns && sub * 8 < rank_j) {             // columns past the adapter's own rank stay zero
-            if (rq == j && row < 64 * MB) tv = *(const u32x4*)(S_tile + (int64_t)min(row, rows_valid - 1) * r + sub * 8);
-            bv = *(const u32x4*)(B + ((int64_t)gj * N + n0 + min(row, cols_valid - 1)) * r + sub * 8);
-        }
-        char* dst = smem + ((cc & 8) ? STAGE_BYTES - lo : lo) + row_slab_off(row, cc & 7);
-        if (row < 64 * MB) *(u32x4*)dst = tv;
-        *(u32x4*)(dst + TILE_BYTES) = bv;
-    }
-    __syncthreads();
-    return nruns * (r >> 4);
-}
-
 // ---- operation (2): Y = X W + S' B ---------------------------------------------------------------
 template <int MB>
 __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
@@ -448,24 +403,48 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
         slab_step<false, MB>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
                          smem + nxt + out_org, fl, nx);
     }
-    if (has_lora) {
+    if (has_lora && !gm.mixed) {
         const int lo = (nk & 1) * STAGE_BYTES;         // the stage that holds the LoRA slab
-        int nkk = p.tb.rank[rt.g] >> 4;
-        if (gm.mixed) {
-            // a tile with several adapters: both stages are rebuilt as one wide LoRA slab pair (below)
-            nkk = build_mixed_lora_slabs<MB>(smem, lo, Ssrc, p.B, p.N, n0, p.r, rt.rows, cols_valid, gm, p.tb);
-            read_frags<false>(f0, smem + lo + tok_org, smem + lo + out_org, fl, fl.row_off[0], 0);
-        }
+        const int nkk = p.tb.rank[rt.g] >> 4;
         mma_frags(acc, f0);
         const int l = threadIdx.x & 63;
 #pragma unroll 1
         for (int kk = 1; kk < nkk; ++kk) {
-            // sub-steps 4..7 (mixed tiles only) live in the other stage
-            const int st = (kk & 4) ? STAGE_BYTES - lo : lo;
             Frags<MB> f;
-            read_frags<false>(f, smem + st + tok_org, smem + st + out_org, fl,
-                              row_slab_off(l & 31, 2 * (kk & 3) + (l >> 5)), 0);
+            read_frags<false>(f, smem + lo + tok_org, smem + lo + out_org, fl, row_slab_off(l & 31, 2 * kk + (l >> 5)), 0);
             mma_frags(acc, f);
+        }
+    } else if (has_lora) {
+        // A tile that holds several adapters (FusedMultiLoRA with tiles cut uniformly over the packed
+        // batch): one run of 64-row groups per adapter.  The S' slab of the whole tile is loaded once, the
+        // B slab once per run, and a run's sub-steps go only to the 32-row blocks inside it, so that no
+        // value of one adapter ever meets a row of another - not even multiplied by zero.
+        const int lo = (nk & 1) * STAGE_BYTES;
+        const int l = threadIdx.x & 63;
+        const int nq = (rt.rows + 63) >> 6;
+        for (int q = 0; q < nq;) {
+            const int g = group_adapter(gm, q);
+            int qe = q + 1;
+            while (qe < nq && group_adapter(gm, qe) == g) ++qe;
+            __syncthreads();                           // every wave is done with the stage's previous contents
+            if (q == 0) load_slab<2 * MB>(lds0 + lo, Ssrc, ss);
+            load_slab(lds0 + lo + TILE_BYTES, p.B + ((int64_t)g * p.N + n0) * p.r, sb);
+            wait_slab_loads();
+            __syncthreads();
+            const int nkk = p.tb.rank[g] >> 4;
+#pragma unroll 1
+            for (int kk = 0; kk < nkk; ++kk) {
+                Frags<MB> f;
+                read_frags<false>(f, smem + lo + tok_org, smem + lo + out_org, fl, row_slab_off(l & 31, 2 * kk + (l >> 5)), 0);
+#pragma unroll
+                for (int mi = 0; mi < MB; ++mi) {
+                    const int blk = wm * (32 * MB) + mi * 32;           // first tile row of the block
+                    if (blk < 64 * q || blk >= 64 * qe) continue;
+#pragma unroll
+                    for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = LF_MFMA(f.fo[ni], f.ft[mi], acc[mi][ni]);
+                }
+            }
+            q = qe;
         }
     }
     store_tile(acc, p.Y, p.N, rt.row_start, rt.rows, n0, cols_valid, wm, wn, smem);
@@ -600,22 +579,6 @@ static bool boundaries_on_64(const AdapterTable& tb) {
     return true;
 }
 
-// Largest number of adapter runs (maximal sequences of 64-row groups with one adapter) in any uniform tile.
-static int max_runs_per_tile(const AdapterTable& tb, int M, int bm) {
-    int worst = 1;
-    for (int t0 = 0; t0 < M; t0 += bm) {
-        int runs = 0, prev = -1;
-        for (int row = t0; row < t0 + bm && row < M; row += 64) {
-            int g = 0;
-            while (g + 1 < tb.G && row >= tb.row0[g + 1]) ++g;
-            if (g != prev) ++runs;
-            prev = g;
-        }
-        if (runs > worst) worst = runs;
-    }
-    return worst;
-}
-
 static int count_row_tiles(const AdapterTable& tb, int gran) {
     int n = 0;
     for (int g = 0; g < tb.G; ++g) n += (tb.row0[g + 1] - tb.row0[g] + gran - 1) / gran;
@@ -625,25 +588,24 @@ static int count_row_tiles(const AdapterTable& tb, int gran) {
 // Row tiling of one launch: uniform tiles over the packed batch or per-segment tiles, of 256 or 128 rows.
 struct RowTiling { int bm; int uniform; int tiles_m; };
 
-// lora_cols_cap: most LoRA contraction columns a mixed tile may hold (0: no limit).
-static int g_forced_row_tile = 0;      // 0: chosen per launch; 128 or 256: fixed (tuning and tests)
-void force_row_tile(int rows) { g_forced_row_tile = rows; }
-int forced_row_tile() { return g_forced_row_tile; }
+static std::atomic<int> g_forced_row_tile{0};      // 0: chosen per launch; 128 or 256: fixed (tuning and tests)
+void force_row_tile(int rows) { g_forced_row_tile.store(rows, std::memory_order_relaxed); }
+int forced_row_tile() { return g_forced_row_tile.load(std::memory_order_relaxed); }
 
-static RowTiling plan_row_tiles(const AdapterTable& tb, int M, int r, int tiles_n, int lora_cols_cap) {
+static RowTiling plan_row_tiles(const AdapterTable& tb, int M, int tiles_n, int forced) {
     RowTiling best{256, 0, 0};
     double best_cost = 0.0;
     const bool on64 = tb.G > 1 && boundaries_on_64(tb);
     for (int bm = 256; bm >= 128; bm >>= 1) {
-        if (g_forced_row_tile != 0 && bm != g_forced_row_tile) continue;
+        if (forced != 0 && bm != forced) continue;
         RowTiling t{bm, 0, 0};
-        t.uniform = on64 && (lora_cols_cap == 0 || max_runs_per_tile(tb, M, bm) * r <= lora_cols_cap);
+        t.uniform = on64;
         t.tiles_m = t.uniform ? (M + bm - 1) / bm : count_row_tiles(tb, bm);
         // rounds of workgroups over the compute units, times the relative duration of one tile (a 128-row
         // tile does half the work of a 256-row one at a lower rate: the out operand is re-read twice as often)
         const int64_t wgs = (int64_t)t.tiles_m * tiles_n;
         const double cost = (double)((wgs + kComputeUnits - 1) / kComputeUnits) * (bm == 256 ? 1.0 : 0.6);
-        if (bm == 256 || g_forced_row_tile != 0 || cost < best_cost) { best = t; best_cost = cost; }
+        if (bm == 256 || forced != 0 || cost < best_cost) { best = t; best_cost = cost; }
     }
     return best;
 }
@@ -659,10 +621,9 @@ static hipError_t launch_gemm(K kernel, bool& attr_set, const A& a, hipStream_t 
     return hipGetLastError();
 }
 
-hipError_t launch_fwd_gemm(FwdGemmArgs a, hipStream_t st) {
+hipError_t launch_fwd_gemm(FwdGemmArgs a, int forced, hipStream_t st) {
     a.tiles_n = (a.N + BN - 1) / BN;
-    // a mixed tile's LoRA step holds runs * r contraction columns in the two LDS stages: at most 128
-    const RowTiling t = plan_row_tiles(a.tb, a.M, a.r, a.tiles_n, 128);
+    const RowTiling t = plan_row_tiles(a.tb, a.M, a.tiles_n, forced);
     a.uniform_tiles = t.uniform;
     a.tiles_m = t.tiles_m;
     if (a.tiles_m == 0) return hipSuccess;
@@ -671,9 +632,9 @@ hipError_t launch_fwd_gemm(FwdGemmArgs a, hipStream_t st) {
                        : launch_gemm(fwd_gemm_kernel<2>, attr_set[1], a, st);
 }
 
-hipError_t launch_bwd_dx(DxGemmArgs a, hipStream_t st) {
+hipError_t launch_bwd_dx(DxGemmArgs a, int forced, hipStream_t st) {
     a.tiles_n = (a.K + BN - 1) / BN;
-    const RowTiling t = plan_row_tiles(a.tb, a.M, a.r, a.tiles_n, 0);
+    const RowTiling t = plan_row_tiles(a.tb, a.M, a.tiles_n, forced);
     a.uniform_tiles = t.uniform;
     a.tiles_m = t.tiles_m;
     if (a.tiles_m == 0) return hipSuccess;

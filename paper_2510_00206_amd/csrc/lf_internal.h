@@ -35,7 +35,7 @@ struct StreamArgs {
     int M, C, r;               // C = N for (3), K for (4)
     int tiles_m, chunks;
     AdapterTable tb;
-    int panel_rows = 0;        // set by the launcher: rows per panel (stream_panel_rows)
+    int panel_rows = 0;        // rows per panel (stream_panel_rows), chosen once per entry-point call
 };
 
 // Reductions of the partials.
@@ -45,7 +45,7 @@ struct FinalizeArgs {
     const float* part_da; float* dA;            // dA[g,c,j] (+)= q_g * sum over the row tiles of segment g
     int M, K, N, r, chunks, accumulate;
     AdapterTable tb;
-    int panel_rows_db = 0, panel_rows_da = 0;   // set by the launchers: the panel heights operations (3) / (4) ran with
+    int panel_rows_db = 0, panel_rows_da = 0;   // the panel heights operations (3) / (4) ran with (same call, same values)
 };
 
 // Operation (5).
@@ -61,18 +61,18 @@ constexpr int kComputeUnits = 256;   // of the one chip this library is written 
 constexpr int kStreamChunk = 512;    // column-chunk width of the streaming kernel
 
 void force_row_tile(int rows);        // 0 (automatic), or the small (128) / large (256) height of every kernel that has two
-int forced_row_tile();
+int forced_row_tile();                // an entry point reads this ONCE and hands the value to everything it launches
 
 // Rows per panel of a streaming reduction over a [M, C] activation.  Every panel leaves an fp32 partial
 // of C x r (dB) or r x C (dA) values, so taller panels mean less partial traffic, while a launch with
 // fewer workgroups than compute units is bound by the latency of one workgroup's sweep: the height is
 // the largest of 1024 .. 64 that still gives about one workgroup per compute unit (256 at least when
-// the large kernel heights are forced).  Used by the launcher of the streaming kernel and by the
-// finalize launchers (same inputs, same answer).
+// the large kernel heights are forced).  Evaluated once per entry-point call; the streaming launch and
+// the finalize launch that adds its partial planes both receive the result.
 constexpr int kStreamFill = 224;     // workgroups that count as "about one per compute unit"
-inline int stream_panel_rows(const AdapterTable& tb, int C) {
+inline int stream_panel_rows(const AdapterTable& tb, int C, int forced) {
     const int chunks = (C + kStreamChunk - 1) / kStreamChunk;
-    const int lowest = forced_row_tile() == 256 ? kRowTile : 64;
+    const int lowest = forced == 256 ? kRowTile : 64;
     for (int rows = 4 * kRowTile; rows > lowest; rows >>= 1)
         if (count_panels(tb, rows) * chunks >= kStreamFill) return rows;
     return lowest;
@@ -88,13 +88,15 @@ inline int64_t max_stream_panels(int64_t M, int G) {
     return tall > low ? tall : low;
 }
 
-hipError_t launch_down(const DownArgs& a, hipStream_t st);
-hipError_t launch_fwd_gemm(FwdGemmArgs a, hipStream_t st);
+// `forced`: the row-tile knob as read by the entry point (0, 128 or 256).  The streaming launchers need
+// StreamArgs::panel_rows, the finalize launchers FinalizeArgs::panel_rows_db / _da, filled in by the caller.
+hipError_t launch_down(const DownArgs& a, int forced, hipStream_t st);
+hipError_t launch_fwd_gemm(FwdGemmArgs a, int forced, hipStream_t st);
 hipError_t launch_stream_dsdb(StreamArgs a, hipStream_t st);
 hipError_t launch_stream_da(StreamArgs a, hipStream_t st);
 hipError_t launch_finalize_ds_db(const FinalizeArgs& a, hipStream_t st);
 hipError_t launch_finalize_da(const FinalizeArgs& a, hipStream_t st);
-hipError_t launch_bwd_dx(DxGemmArgs a, hipStream_t st);
+hipError_t launch_bwd_dx(DxGemmArgs a, int forced, hipStream_t st);
 hipError_t launch_debug_mask(int64_t M, int64_t K, uint32_t T, uint32_t k0, uint32_t k1, uint8_t* keep,
                              hipStream_t st);
 

@@ -242,13 +242,17 @@ template <int CB, bool IS_DA>
 static hipError_t launch_stream_t(StreamArgs a, hipStream_t st) {
     constexpr int R = CB * 16;
     const int lds = ST_BIG_BYTES + ST_STEP * R * 2 + (IS_DA ? 0 : kStreamChunk * R * 2 + 4 * CB * 64 * 16);
-    a.panel_rows = stream_panel_rows(a.tb, a.C);
+    if (a.panel_rows < ST_STEP) return hipErrorInvalidValue;
     a.tiles_m = count_panels(a.tb, a.panel_rows);
     a.chunks = (a.C + kStreamChunk - 1) / kStreamChunk;
     if (a.tiles_m == 0) return hipSuccess;
-    hipError_t e = hipFuncSetAttribute((const void*)stream_kernel<CB, IS_DA>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
+    static bool attr_set = false;                      // one flag per instantiation
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)stream_kernel<CB, IS_DA>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
     hipLaunchKernelGGL((stream_kernel<CB, IS_DA>), dim3(a.tiles_m * a.chunks), dim3(ST_THREADS), lds, st, a);
     return hipGetLastError();
 }
@@ -331,17 +335,15 @@ hipError_t launch_finalize_ds_db(const FinalizeArgs& a, hipStream_t st) {
     const int64_t n_db = a.part_db ? (int64_t)a.tb.G * a.N * (a.r >> 2) : 0;
     if (n_ds + n_db == 0) return hipSuccess;
     const int blocks_ds = (int)((n_ds + 255) / 256), blocks_db = (int)((n_db + 255) / 256);
-    FinalizeArgs b = a;
-    b.panel_rows_db = stream_panel_rows(a.tb, a.N);
-    hipLaunchKernelGGL(finalize_ds_db_kernel, dim3(blocks_ds + blocks_db), dim3(256), 0, st, b, blocks_ds);
+    if (n_db && a.panel_rows_db < ST_STEP) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(finalize_ds_db_kernel, dim3(blocks_ds + blocks_db), dim3(256), 0, st, a, blocks_ds);
     return hipGetLastError();
 }
 
 hipError_t launch_finalize_da(const FinalizeArgs& a, hipStream_t st) {
     const int64_t n = (int64_t)a.tb.G * a.r * (a.K >> 2);
-    FinalizeArgs b = a;
-    b.panel_rows_da = stream_panel_rows(a.tb, a.K);
-    hipLaunchKernelGGL(finalize_da_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, b);
+    if (a.panel_rows_da < ST_STEP) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(finalize_da_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 

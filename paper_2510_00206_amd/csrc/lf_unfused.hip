@@ -149,19 +149,20 @@ lora_status lora_unfused_fwd(const lora_bf16* X, const lora_bf16* W, const lora_
     if (workspace_bytes < ws.bytes) return LORA_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     const AdapterTable real = make_table(M, r, s, p, seed, false), plain = make_table(M, r, s, p, seed, true);
+    const int forced = forced_row_tile();
     // 1. Xhat = dropout(X)
     hipLaunchKernelGGL(dropout_kernel, dim3(blocks_for(M * (K >> 3))), dim3(EW_THREADS), 0, st, X, ws.Xhat, M, (int)K,
                        real.T[0], real.q[0], real.k0[0], real.k1[0]);
     LF_LAUNCHED();
     // 2. S = Xhat A^T
-    LF_TRY(launch_down(DownArgs{ws.Xhat, A, ws.S, (int)M, (int)K, r, plain}, st));
+    LF_TRY(launch_down(DownArgs{ws.Xhat, A, ws.S, (int)M, (int)K, r, plain}, forced, st));
     // 3. Y2 = S B^T
-    LF_TRY(launch_fwd_gemm(FwdGemmArgs{nullptr, nullptr, ws.S, B, ws.Y2, (int)M, 0, (int)N, r, 0, 0, plain}, st));
+    LF_TRY(launch_fwd_gemm(FwdGemmArgs{nullptr, nullptr, ws.S, B, ws.Y2, (int)M, 0, (int)N, r, 0, 0, plain}, forced, st));
     // 4. Y2 *= s
     hipLaunchKernelGGL(scale_kernel, dim3(blocks_for(M * N / 8)), dim3(EW_THREADS), 0, st, ws.Y2, ws.Y2, M * N / 8, s);
     LF_LAUNCHED();
     // 5. Y1 = X W^T
-    LF_TRY(launch_fwd_gemm(FwdGemmArgs{X, W, nullptr, nullptr, ws.Y1, (int)M, (int)K, (int)N, 0, 0, 0, plain}, st));
+    LF_TRY(launch_fwd_gemm(FwdGemmArgs{X, W, nullptr, nullptr, ws.Y1, (int)M, (int)K, (int)N, 0, 0, 0, plain}, forced, st));
     // 6. Y = Y1 + Y2
     hipLaunchKernelGGL(add_kernel, dim3(blocks_for(M * N / 8)), dim3(EW_THREADS), 0, st, ws.Y1, ws.Y2, Y, M * N / 8);
     LF_LAUNCHED();
@@ -180,28 +181,30 @@ lora_status lora_unfused_bwd(const lora_bf16* W, const lora_bf16* A, const lora_
     hipStream_t st = (hipStream_t)stream;
     const AdapterTable real = make_table(M, r, s, p, seed, false), plain = make_table(M, r, s, p, seed, true);
     const int chunks = (int)((N + kStreamChunk - 1) / kStreamChunk);
+    const int forced = forced_row_tile();
+    const int rows_db = stream_panel_rows(plain, (int)N, forced), rows_da = stream_panel_rows(plain, (int)K, forced);
     // 1. dY2 = s dY
     hipLaunchKernelGGL(scale_kernel, dim3(blocks_for(M * N / 8)), dim3(EW_THREADS), 0, st, dY, ws.dY2, M * N / 8, s);
     LF_LAUNCHED();
     // 2. dB = dY2^T S     3. dS = dY2 B      (one pass over dY2 each)
-    LF_TRY(launch_stream_dsdb(StreamArgs{ws.dY2, ws.S, B, ws.part_db, nullptr, (int)M, (int)N, r, 0, 0, plain}, st));
+    LF_TRY(launch_stream_dsdb(StreamArgs{ws.dY2, ws.S, B, ws.part_db, nullptr, (int)M, (int)N, r, 0, 0, plain, rows_db}, st));
     LF_TRY(launch_finalize_ds_db(FinalizeArgs{nullptr, nullptr, ws.part_db, dB, nullptr, nullptr,
-                                              (int)M, (int)K, (int)N, r, chunks, 0, plain}, st));
-    LF_TRY(launch_stream_dsdb(StreamArgs{ws.dY2, ws.S, B, nullptr, ws.part_ds, (int)M, (int)N, r, 0, 0, plain}, st));
+                                              (int)M, (int)K, (int)N, r, chunks, 0, plain, rows_db, rows_da}, st));
+    LF_TRY(launch_stream_dsdb(StreamArgs{ws.dY2, ws.S, B, nullptr, ws.part_ds, (int)M, (int)N, r, 0, 0, plain, rows_db}, st));
     LF_TRY(launch_finalize_ds_db(FinalizeArgs{ws.part_ds, ws.dS, nullptr, nullptr, nullptr, nullptr,
-                                              (int)M, (int)K, (int)N, r, chunks, 0, plain}, st));
+                                              (int)M, (int)K, (int)N, r, chunks, 0, plain, rows_db, rows_da}, st));
     // 4. dA = Xhat^T dS
-    LF_TRY(launch_stream_da(StreamArgs{ws.Xhat, ws.dS, nullptr, ws.part_da, nullptr, (int)M, (int)K, r, 0, 0, plain}, st));
+    LF_TRY(launch_stream_da(StreamArgs{ws.Xhat, ws.dS, nullptr, ws.part_da, nullptr, (int)M, (int)K, r, 0, 0, plain, rows_da}, st));
     LF_TRY(launch_finalize_da(FinalizeArgs{nullptr, nullptr, nullptr, nullptr, ws.part_da, dA,
-                                           (int)M, (int)K, (int)N, r, chunks, 0, plain}, st));
+                                           (int)M, (int)K, (int)N, r, chunks, 0, plain, rows_db, rows_da}, st));
     // 5. dXhat = dS A
-    LF_TRY(launch_bwd_dx(DxGemmArgs{nullptr, nullptr, ws.dS, A, ws.dXhat, (int)M, (int)K, 0, r, 0, 0, plain}, st));
+    LF_TRY(launch_bwd_dx(DxGemmArgs{nullptr, nullptr, ws.dS, A, ws.dXhat, (int)M, (int)K, 0, r, 0, 0, plain}, forced, st));
     // 6. dXhat = mask * q * dXhat
     hipLaunchKernelGGL(mask_scale_kernel, dim3(blocks_for(M * (K >> 3))), dim3(EW_THREADS), 0, st, ws.dXhat, M, (int)K,
                        real.T[0], real.q[0], real.k0[0], real.k1[0]);
     LF_LAUNCHED();
     // 7. dX1 = dY W
-    LF_TRY(launch_bwd_dx(DxGemmArgs{dY, W, nullptr, nullptr, ws.dX1, (int)M, (int)K, (int)N, 0, 0, 0, plain}, st));
+    LF_TRY(launch_bwd_dx(DxGemmArgs{dY, W, nullptr, nullptr, ws.dX1, (int)M, (int)K, (int)N, 0, 0, 0, plain}, forced, st));
     // 8. dX = dX1 + dXhat
     hipLaunchKernelGGL(add_kernel, dim3(blocks_for(M * K / 8)), dim3(EW_THREADS), 0, st, ws.dX1, ws.dXhat, dX, M * K / 8);
     LF_LAUNCHED();
@@ -213,7 +216,7 @@ lora_status lora_frozen_fwd(const lora_bf16* X, const lora_bf16* W, int64_t M, i
     if (!X || !W || !Y) return LORA_ERR_NULL;
     if (!supported(M, K, N, 16)) return LORA_ERR_UNSUPPORTED;
     const AdapterTable plain = make_table(M, 0, 1.f, 0.f, 0, true);
-    LF_TRY(launch_fwd_gemm(FwdGemmArgs{X, W, nullptr, nullptr, Y, (int)M, (int)K, (int)N, 0, 0, 0, plain}, (hipStream_t)stream));
+    LF_TRY(launch_fwd_gemm(FwdGemmArgs{X, W, nullptr, nullptr, Y, (int)M, (int)K, (int)N, 0, 0, 0, plain}, forced_row_tile(), (hipStream_t)stream));
     return LORA_OK;
 }
 
@@ -222,7 +225,7 @@ lora_status lora_frozen_bwd(const lora_bf16* dY, const lora_bf16* W, int64_t M, 
     if (!dY || !W || !dX) return LORA_ERR_NULL;
     if (!supported(M, K, N, 16)) return LORA_ERR_UNSUPPORTED;
     const AdapterTable plain = make_table(M, 0, 1.f, 0.f, 0, true);
-    LF_TRY(launch_bwd_dx(DxGemmArgs{dY, W, nullptr, nullptr, dX, (int)M, (int)K, (int)N, 0, 0, 0, plain}, (hipStream_t)stream));
+    LF_TRY(launch_bwd_dx(DxGemmArgs{dY, W, nullptr, nullptr, dX, (int)M, (int)K, (int)N, 0, 0, 0, plain}, forced_row_tile(), (hipStream_t)stream));
     return LORA_OK;
 }
 

@@ -72,6 +72,8 @@ def test_mask_is_read_back_bit_exact_through_dx_and_s():
 
 
 def test_p0_b0_is_the_frozen_linear():
+    """p = 0 and B = 0: Y = X W and dX = dY W^T - the plain products, and the same bits as the library's own
+    frozen-linear GEMMs (the LoRA steps add exact zeros to the same accumulation order); dA = 0."""
     L = workloads.custom_layer(320, 256, 192, 16, 2.0, 0.0, cfg=5)
     X, W, A, B, dY = workloads.make_inputs(L)
     B = torch.zeros_like(B)
@@ -80,6 +82,55 @@ def test_p0_b0_is_the_frozen_linear():
     assert rel_err(gpu["Y"], f64(X) @ f64(W).T) <= TOL / 4
     assert rel_err(gpu["dX"], f64(dY) @ f64(W)) <= TOL / 4
     assert not gpu["dA"].any()
+    assert torch.equal(gpu["Y"], binding.frozen_fwd(X.cuda(), W.cuda()))
+    assert torch.equal(gpu["dX"], binding.frozen_bwd(dY.cuda(), W.cuda()))
+
+
+ISOLATION = [  # M, K, N, r, segment lengths (boundaries on 64: uniform tiles that hold several adapters), poisoned adapter
+    (832, 256, 320, 16, (64, 64, 64, 64, 192, 0, 64, 320), 2),
+    (704, 192, 448, 32, (64, 64, 64, 64, 128, 192, 128), 1),
+    (576, 256, 256, 64, (64, 128, 64, 320), 1),
+    (768, 320, 576, 64, (128, 64, 64, 256, 256), 3),
+    (601, 320, 192, 32, (100, 37, 300, 164), 2),          # boundaries off the grid: per-segment tiles
+]
+
+
+@pytest.mark.parametrize("case", ISOLATION, ids=lambda c: "x".join(str(v) for v in c[:4]))
+@pytest.mark.parametrize("poison", ["nan", "inf"])
+def test_adapters_do_not_interfere_under_non_finite_values(case, poison):
+    """One adapter of a packed batch has diverged: its A and B hold NaN (or +-Inf).  Every other
+    segment's Y, S', dX, dA and dB must stay what its single-adapter call gives, bit for bit
+    (Section 5.1, FusedMultiLoRA: independent jobs share the kernels without interference)."""
+    M, K, N, r, lens, bad = case
+    L = workloads.custom_layer(M, K, N, r, 2.0, 0.1, seg_lens=lens, cfg=14)
+    print(f"isolation {L} poison={poison} adapter={bad}", flush=True)
+    X, W, A, B, dY = workloads.make_inputs(L)
+    A, B = A.clone(), B.clone()
+    if poison == "nan":
+        A[bad], B[bad] = float("nan"), float("nan")
+    else:
+        A[bad, ::2], A[bad, 1::2] = float("inf"), float("-inf")
+        B[bad, ::2], B[bad, 1::2] = float("-inf"), float("inf")
+    s = [0.5 + g for g in range(L.G)]
+    p = [0.05 * (g + 1) for g in range(L.G)]
+    dev = "cuda"
+    Xg, Wg, Ag, Bg, dYg = (t.to(dev) for t in (X, W, A, B, dY))
+    Y, S = binding.multi_lora_fwd(Xg, Wg, Ag, Bg, L.seg_offsets, s, p, L.seeds)
+    dX, dA, dB = binding.multi_lora_bwd(Xg, Wg, Ag, Bg, S, dYg, L.seg_offsets, s, p, L.seeds)
+    torch.cuda.synchronize()
+    o = L.seg_offsets
+    assert o[bad + 1] > o[bad]
+    assert not torch.isfinite(Y[o[bad]:o[bad + 1]]).all()          # the poison is really there
+    for g in range(L.G):
+        if g == bad or o[g + 1] == o[g]:
+            continue
+        sl = slice(o[g], o[g + 1])
+        Y1, S1 = binding.lora_fwd(Xg[sl].contiguous(), Wg, Ag[g].contiguous(), Bg[g].contiguous(), s[g], p[g], L.seeds[g])
+        dX1, dA1, dB1 = binding.lora_bwd(Xg[sl].contiguous(), Wg, Ag[g].contiguous(), Bg[g].contiguous(), S1,
+                                         dYg[sl].contiguous(), s[g], p[g], L.seeds[g])
+        for name, one, packed in (("Y", Y1, Y[sl]), ("S", S1, S[sl]), ("dX", dX1, dX[sl]), ("dA", dA1, dA[g]), ("dB", dB1, dB[g])):
+            assert torch.isfinite(packed).all(), (g, name)
+            assert torch.equal(one, packed), (g, name)
 
 
 MULTI = [  # M, K, N, r, segment lengths

@@ -83,3 +83,44 @@ def test_kernel_heights_agree(lens, r, ranks):
             assert torch.equal(a, b), name
         for a, b, name in zip(outs[0][3:], other[3:], ("dA", "dB")):
             assert rel_err(a, f64(b)) <= 1e-5, name
+
+
+def test_row_tile_knob_is_read_once_per_call():
+    """Another thread flips the kernel-height knob while backward calls are in flight: every call must
+    still pair each streaming launch with a finalize launch of the same panel height, i.e. return one
+    of the two results the fixed settings give (a mismatch would add the wrong partial planes)."""
+    import threading
+    L = workloads.custom_layer(1100, 256, 192, 16, 1.0, 0.1, cfg=15)
+    Xg, Wg, Ag, Bg, dYg = (t.cuda() for t in workloads.make_inputs(L))
+    A1, B1 = Ag[0].contiguous(), Bg[0].contiguous()
+    _, S = binding.lora_fwd(Xg, Wg, A1, B1, L.s, L.p, L.seeds[0])
+    ws = binding.alloc_workspace(L.M, L.K, L.N, L.r)
+    want = []
+    try:
+        for rows in (0, 256):
+            binding.lora_set_row_tile(rows)
+            _, dA, dB = binding.lora_bwd(Xg, Wg, A1, B1, S, dYg, L.s, L.p, L.seeds[0], need_dx=False, workspace=ws)
+            torch.cuda.synchronize()
+            want.append((dA.clone(), dB.clone()))
+        assert not torch.equal(want[0][0], want[1][0])           # the two heights really sum in different orders
+        stop = threading.Event()
+
+        def flip():
+            i = 0
+            while not stop.is_set():
+                binding.lora_set_row_tile(256 if i & 1 else 0)
+                i += 1
+
+        th = threading.Thread(target=flip)
+        th.start()
+        try:
+            print("knob flips during 300 backward calls", flush=True)
+            for it in range(300):
+                _, dA, dB = binding.lora_bwd(Xg, Wg, A1, B1, S, dYg, L.s, L.p, L.seeds[0], need_dx=False, workspace=ws)
+                torch.cuda.synchronize()
+                assert any(torch.equal(dA, a) and torch.equal(dB, b) for a, b in want), it
+        finally:
+            stop.set()
+            th.join()
+    finally:
+        binding.lora_set_row_tile(0)
