@@ -81,18 +81,38 @@ struct Workspace {
     lora_bf16* dS; float* part_ds; float* part_db; float* part_da; size_t bytes;
 };
 
-Workspace carve(void* base, int64_t M, int64_t K, int64_t N, int32_t r, int32_t G) {
-    const int64_t tiles = max_stream_panels(M, G);               // upper bound on row panels
+// planes_db / planes_da: fp32 planes of dB / dA partials to provide for (one per row panel)
+Workspace carve(void* base, int64_t M, int64_t K, int64_t N, int32_t r, int64_t planes_db, int64_t planes_da) {
     const int64_t chunks = (N + kStreamChunk - 1) / kStreamChunk;
     size_t off = 0;
     Workspace w;
     char* b = (char*)base;
     w.dS = (lora_bf16*)(b + off);      off += align_up((size_t)M * r * 2);
     w.part_ds = (float*)(b + off);     off += align_up((size_t)chunks * M * r * 4);
-    w.part_db = (float*)(b + off);     off += align_up((size_t)tiles * N * r * 4);
-    w.part_da = (float*)(b + off);     off += align_up((size_t)tiles * r * K * 4);
+    w.part_db = (float*)(b + off);     off += align_up((size_t)planes_db * N * r * 4);
+    w.part_da = (float*)(b + off);     off += align_up((size_t)planes_da * r * K * 4);
     w.bytes = off;
     return w;
+}
+
+// The caller-provided workspace is sized before the call's panel heights are known: for the most panels
+// any launch over M rows in G segments can choose.
+Workspace carve(void* base, int64_t M, int64_t K, int64_t N, int32_t r, int32_t G) {
+    const int64_t tiles = max_stream_panels(M, G);
+    return carve(base, M, K, N, r, tiles, tiles);
+}
+
+// What one backward call launches with: the knob is read once and the panel heights are chosen here, for
+// the streaming launches and for the finalize launches that add their partial planes, so that a change
+// of the knob by another thread in the middle of a call cannot make the two disagree.
+struct BwdPlan { int forced, rows_db, rows_da; };
+
+BwdPlan plan_bwd(const AdapterTable& tb, int64_t K, int64_t N) {
+    BwdPlan pl;
+    pl.forced = forced_row_tile();
+    pl.rows_db = stream_panel_rows(tb, (int)N, pl.forced);
+    pl.rows_da = stream_panel_rows(tb, (int)K, pl.forced);
+    return pl;
 }
 
 lora_status fwd_impl(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
@@ -109,14 +129,9 @@ lora_status fwd_impl(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A,
 lora_status bwd_impl(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
                      const lora_bf16* S, const lora_bf16* dY, int64_t M, int64_t K, int64_t N, int32_t r,
                      const AdapterTable& tb, lora_bf16* dX, float* dA, float* dB, int accumulate,
-                     void* workspace, hipStream_t st) {
-    const Workspace ws = carve(workspace, M, K, N, r, tb.G);
+                     const Workspace& ws, const BwdPlan& pl, hipStream_t st) {
     const int chunks = (int)((N + kStreamChunk - 1) / kStreamChunk);
-    // The knob is read once per call and the panel heights are chosen here, for the streaming launches
-    // and for the finalize launches that add their partial planes: a change of the knob by another
-    // thread in the middle of this call cannot make the two disagree.
-    const int forced = forced_row_tile();
-    const int rows_db = stream_panel_rows(tb, (int)N, forced), rows_da = stream_panel_rows(tb, (int)K, forced);
+    const int forced = pl.forced, rows_db = pl.rows_db, rows_da = pl.rows_da;
     StreamArgs s3{dY, S, B, ws.part_db, ws.part_ds, (int)M, (int)N, r, 0, 0, tb, rows_db};
     if (timed(LORA_PROF_DS_DB, st, [&] { return launch_stream_dsdb(s3, st); }) != hipSuccess) return LORA_ERR_HIP;
     FinalizeArgs fin{ws.part_ds, ws.dS, ws.part_db, dB, ws.part_da, dA,
@@ -190,8 +205,9 @@ lora_status multi_lora_bwd_ranked(const lora_bf16* X, const lora_bf16* W, const 
     AdapterTable tb;
     st = build_table(tb, M, r, G, seg_offsets, s, p, seeds, ranks);
     if (st != LORA_OK) return st;
-    if (workspace_bytes < carve(nullptr, M, K, N, r, G).bytes) return LORA_ERR_WORKSPACE;
-    return bwd_impl(X, W, A, B, S_saved, dY, M, K, N, r, tb, dX, dA, dB, accumulate, workspace,
+    const Workspace ws = carve(workspace, M, K, N, r, G);
+    if (workspace_bytes < ws.bytes) return LORA_ERR_WORKSPACE;
+    return bwd_impl(X, W, A, B, S_saved, dY, M, K, N, r, tb, dX, dA, dB, accumulate, ws, plan_bwd(tb, K, N),
                     (hipStream_t)stream);
 }
 
