@@ -38,6 +38,45 @@ def read_traffic(workload: str):
     return None
 
 
+def measure_ceilings(torch, binding, dev, operands):
+    """What this GPU sustains with nothing in the way (library diagnostics, timed with events on the launch
+    stream): the GEMM kernels' MFMA instruction in a register-resident loop on `operands` (values of the
+    workload's distribution), and one plain read of a 2 GiB buffer (eight times the memory-side cache)."""
+    def timed(fn, reps, skip):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        evs[0].record()
+        for i in range(reps):
+            fn()
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(reps)][skip:]
+        return sum(ms) / len(ms)
+
+    big = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+    big.fill_(1)
+    sink2 = torch.empty(4096 * 256, dtype=torch.int32, device=dev)
+    nbytes = [0]
+
+    def read():
+        nbytes[0] = binding.ceiling_hbm_read(big, sink2, 4096)
+    ms = timed(read, 6, 2)
+    read_gbs = nbytes[0] / (ms * 1e-3) / 1e9
+    del big
+
+    # the matrix loop last: the timed steps then start from the chip's state under its heaviest load
+    wgs, iters = 2048, 1536
+    sink = torch.empty(wgs * 256, dtype=torch.float32, device=dev)
+    flops = [0.0]
+
+    def mfma():
+        flops[0] = binding.ceiling_mfma(operands, sink, wgs, iters)
+    ms = timed(mfma, 8, 3)                      # about 60 ms in all: the sustained rate, not the first burst
+    mfma_tflops = flops[0] / (ms * 1e-3) / 1e12
+    return {"mfma_bf16_tflops": round(mfma_tflops, 1), "hbm_read_gbs": round(read_gbs, 1),
+            "how": "register-resident v_mfma_f32_32x32x16_bf16 loop, 16 chains per wave, 1 wave per SIMD, operands = "
+                   "the workload's X values; plain 16-byte-per-lane read of 2 GiB"}
+
+
 def sweep(torch, binding, workloads, dev, args):
     """The axes of the paper's Figure 3 / Figure 17 on this GPU: n = k = 4096, tokens swept, r in {16, 32};
     forward and backward times of the fused LoRA linear, the unfused baseline and the frozen linear."""
@@ -102,6 +141,10 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="record one step (all layers, forward + backward) into a HIP graph and time replays of it: "
                          "takes the host's launch work out of launch-bound workloads such as c1")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the measured ceilings (register-resident MFMA loop, plain HBM read) that are otherwise "
+                         "taken before the warm-up steps")
+    ap.add_argument("--ceilings-only", action="store_true", help="measure and print the ceilings, nothing else")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 1 GiB device copy 10 times (reference reading for HBM byte counters)")
     args = ap.parse_args()
@@ -176,6 +219,14 @@ def main():
                                    st["s"], st["p"], L.seeds, dA=st["dA"], dB=st["dB"],
                                    workspace=st["ws"], dX=st["dX"])
 
+    # measured ceilings first (outside the timed region): they also bring the chip to its working clocks
+    ceilings = None
+    if not args.no_ceilings and not args.unfused:
+        ceilings = measure_ceilings(torch, binding, dev, state[0]["X"])
+        if args.ceilings_only:
+            print(json.dumps({"ceilings": ceilings}))
+            return
+
     eager_step = step
     if args.graph:
         assert len(sets) == 1, "--graph replays one recorded step: use it without --rotate"
@@ -238,6 +289,11 @@ def main():
     dom_flops /= len(state)
     achieved = dom_flops / (kernels_us[dom] * 1e-6) / 1e12
     traffic = read_traffic(args.workload)
+    # the bandwidth-bound kernels: algorithmic bytes (one read of X or dY per launch) over their launch time
+    stream_bytes = {"down": sum(2 * st["L"].M * st["L"].K for st in state) / len(state),
+                    "ds_db": sum(2 * st["L"].M * st["L"].N for st in state) / len(state),
+                    "da": sum(2 * st["L"].M * st["L"].K for st in state) / len(state)}
+    stream_gbs = {k: round(b / (kernels_us[k] * 1e-6) / 1e9, 1) for k, b in stream_bytes.items() if kernels_us[k] > 0}
 
     out = {
         "metric": "fused LoRA linear fwd+bwd TFLOP/s and tokens/s at 1 MI355X; HBM bytes/token",
@@ -264,8 +320,17 @@ def main():
         "kernel_us": {k: round(v, 2) for k, v in kernels_us.items()},
         "kernel_launches": launches,
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic},
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary under profiles/ (not taken by this run)"},
+        "stream_kernels_gbs": stream_gbs,
+        "peak_hbm_gbs": PEAK_HBM_GBS,
     }
+    if ceilings:
+        out["ceilings"] = ceilings
+        out["roofline"]["measured_peak"] = ceilings["mfma_bf16_tflops"]
+        out["roofline"]["frac_of_measured"] = round(achieved / ceilings["mfma_bf16_tflops"], 4)
+        out["frac_of_measured_mfma_peak"] = round(tflops / ceilings["mfma_bf16_tflops"], 4)
+        out["stream_kernels_frac_of_measured_read"] = {k: round(v / ceilings["hbm_read_gbs"], 4) for k, v in stream_gbs.items()}
 
     if not args.no_cpu_baseline:
         import numpy as np

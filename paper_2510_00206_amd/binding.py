@@ -62,6 +62,10 @@ def load_library() -> C.CDLL:
     lib.lora_unfused_fwd.restype = C.c_int
     lib.lora_unfused_bwd.restype = C.c_int
     lib.lora_profile_end.argtypes = [C.POINTER(F), C.POINTER(I32)]
+    lib.lora_ceiling_mfma.argtypes = [P, P, I32, I32, C.POINTER(C.c_double), P]
+    lib.lora_ceiling_mfma.restype = C.c_int
+    lib.lora_ceiling_hbm_read.argtypes = [P, SZ, P, I32, P]
+    lib.lora_ceiling_hbm_read.restype = C.c_int
     for f in ("lora_fwd", "lora_bwd", "multi_lora_fwd", "multi_lora_bwd", "multi_lora_fwd_ranked",
               "multi_lora_bwd_ranked", "lora_debug_mask",
               "lora_profile_begin", "lora_profile_end"):
@@ -248,3 +252,19 @@ def frozen_bwd(dY, W, dX=None):
     dX = torch.empty((M, K), dtype=torch.bfloat16, device=dY.device) if dX is None else dX
     _check(load_library().lora_frozen_bwd(_ptr(dY), _ptr(W), M, K, N, _ptr(dX), _stream()))
     return dX
+
+
+def ceiling_mfma(operands, sink, workgroups, iters) -> float:
+    """Enqueues the register-resident MFMA loop; returns the floating-point operations of the launch."""
+    assert operands.numel() * operands.element_size() >= 65536 and sink.numel() >= workgroups * 256
+    flops = C.c_double()
+    _check(load_library().lora_ceiling_mfma(_ptr(operands), _ptr(sink), workgroups, iters, C.byref(flops), _stream()))
+    return flops.value
+
+
+def ceiling_hbm_read(src, sink, workgroups) -> int:
+    """Enqueues one plain read of `src`; returns the bytes read."""
+    nbytes = src.numel() * src.element_size() // 16 * 16
+    assert sink.numel() >= workgroups * 256
+    _check(load_library().lora_ceiling_hbm_read(_ptr(src), nbytes, _ptr(sink), workgroups, _stream()))
+    return nbytes

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblorafusion_hip.so")
-SOURCES = ["lf_api.hip", "lf_down.hip", "lf_gemm.hip", "lf_stream.hip", "lf_unfused.hip"]
+SOURCES = ["lf_api.hip", "lf_down.hip", "lf_gemm.hip", "lf_stream.hip", "lf_unfused.hip", "lf_ceiling.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

@@ -32,9 +32,15 @@ def _check_layer(L, li, zero_w=False):
     ref = run_oracle(L, *inp)
     compare(gpu, ref, label=f"{L.name} W0={zero_w} (all rows)")
     if zero_w:
-        # operation (5) alone: every kept element carries a generic non-zero LoRA gradient
+        # operation (5) alone: a dropped element is exactly zero; a kept one carries a generic non-zero LoRA
+        # gradient - unless that sum of r products itself cancels (the oracle's value is then tiny; it
+        # happens to about one element in 10^7)
         got = (gpu["dX"] != 0).cpu().numpy()
-        assert np.array_equal(got, _keep_of(L)), f"{L.name}: mask read through dX differs"
+        keep = _keep_of(L)
+        assert not (got & ~keep).any(), f"{L.name}: a dropped element of dX is not zero"
+        lost = ~got & keep
+        assert lost.sum() <= 16 and (np.abs(ref["dX"][lost]) <= 1e-3 * np.abs(ref["dX"]).max()).all(), \
+            f"{L.name}: kept elements of dX are zero ({int(lost.sum())})"
 
 
 @pytest.mark.parametrize("cfg,li", [("c1", 0), ("c2", 0), ("c3", 0), ("c3", 1), ("c3", 2), ("c4", 0), ("c5", 0), ("c5", 1)],
@@ -120,26 +126,31 @@ def test_mask_through_down_projection_full_size(name, M, K, r, p, lens):
 
 
 @pytest.mark.parametrize("name,M,K,r,p,lens", MASK_SHAPES, ids=[s[0] for s in MASK_SHAPES])
-def test_mask_through_da_full_size(name, M, K, r, p, lens):
-    """Operation (4): with X = 1 and dY, B chosen so that the scaled dS is v = bf16(s q) in column 0 and zero
-    elsewhere, dA[g, 0, j] = v * (number of kept rows of segment g in column j), an exact fp32 integer
-    multiple: the column keep counts of the oracle's mask, for every column."""
+def test_mask_through_da_and_dx_full_size(name, M, K, r, p, lens):
+    """Operations (4) and (5): X = 1, W = 0, and dY, B chosen so that the scaled dS is v = bf16(s q) in column 0
+    and zero elsewhere.  Then dA[g, 0, j] = v * (number of kept rows of segment g in column j), an exact fp32
+    integer multiple - the column keep counts of the oracle's mask, for every column - and, with row 0 of A all
+    ones, dX[i, j] = v * keep(i, j) exactly: the whole mask, bit for bit, through the dX kernel."""
     L = workloads.custom_layer(M, K, 64, r, 1.0, p, seg_lens=lens, cfg=62)
     dev = "cuda"
     keep = _keep_of(L)
     X = torch.ones((M, K), dtype=torch.bfloat16, device=dev)
     W = torch.zeros((64, K), dtype=torch.bfloat16, device=dev)
     A = torch.zeros((L.G, r, K), dtype=torch.bfloat16, device=dev)
+    A[:, 0, :] = 1.0
     B = torch.zeros((L.G, 64, r), dtype=torch.bfloat16, device=dev)
     B[:, 0, 0] = 1.0
     dY = torch.zeros((M, 64), dtype=torch.bfloat16, device=dev)
     dY[:, 0] = 1.0
     s, pp = [L.s] * L.G, [p] * L.G
-    print(f"mask via dA {name}", flush=True)
+    print(f"mask via dA and dX {name}", flush=True)
     _, S = binding.multi_lora_fwd(X, W, A, B, L.seg_offsets, s, pp, L.seeds)
-    _, dA, _ = binding.multi_lora_bwd(X, W, A, B, S, dY, L.seg_offsets, s, pp, L.seeds, need_dx=False)
+    dX, dA, _ = binding.multi_lora_bwd(X, W, A, B, S, dY, L.seg_offsets, s, pp, L.seeds)
     torch.cuda.synchronize()
-    v = float(torch.tensor(np.float32(L.s) * np.float32(65536.0 / (65536.0 - oracle.dropout_threshold(p)))).to(torch.bfloat16))
+    vb = torch.tensor(np.float32(L.s) * np.float32(65536.0 / (65536.0 - oracle.dropout_threshold(p)))).to(torch.bfloat16)
+    v = float(vb)
+    want_dx = torch.from_numpy(keep).to(dev) * vb.to(dev)
+    assert torch.equal(dX, want_dx.to(torch.bfloat16)), name
     o = L.seg_offsets
     for g in range(L.G):
         counts = keep[o[g]:o[g + 1]].sum(axis=0).astype(np.float64)
