@@ -55,7 +55,7 @@ typedef enum {
     LORA_ERR_ALIGN = 3,       /* a device pointer is not 16-byte aligned */
     LORA_ERR_PARAM = 4,       /* p outside [0,1), or p/s not finite */
     LORA_ERR_SEGMENTS = 5,    /* offsets do not rise from 0 to M */
-    LORA_ERR_WORKSPACE = 6,   /* workspace smaller than lora_bwd_workspace_bytes() */
+    LORA_ERR_WORKSPACE = 6,   /* workspace smaller than lora_bwd_workspace_bytes(); lora_bwd_noalloc: beyond its scratch */
     LORA_ERR_UNSUPPORTED = 7, /* K or N not a multiple of 64 or above 2^22, r not in {16,32,64}, G > 64 */
     LORA_ERR_HIP = 8          /* a kernel launch failed */
 } lora_status;
@@ -83,6 +83,22 @@ lora_status lora_bwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A,
                      int64_t M, int64_t K, int64_t N, int32_t r, float s, float p, uint64_t seed,
                      lora_bf16* dX, float* dA, float* dB, int accumulate,
                      void* workspace, size_t workspace_bytes, lora_stream stream);
+
+/* The same backward for callers that cannot allocate or carry device scratch: code that runs under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Instead of a workspace argument
+ * the kernels use an array of LORA_NOALLOC_SCRATCH_BYTES that is part of the library's device image (each
+ * GPU the library runs on holds one from the first call on it until the process ends); the call itself
+ * allocates and frees nothing and enqueues no memset.  Arguments, results (bit for bit) and errors are
+ * those of lora_bwd, except: a problem whose partial sums do not fit the array - dS (2 M r bytes), its
+ * per-column-chunk partials (4 M r ceil(N/512)) and one fp32 plane of dB and of dA per row panel - returns
+ * LORA_ERR_WORKSPACE and enqueues nothing (M = 8192, K = N = 4096, r = 16 needs 20.3 MiB).  All calls on
+ * one GPU share that GPU's array: two calls that overlap in time on one GPU (different streams, or
+ * replays of graphs that hold such a call) race; calls on one stream are ordered and safe. */
+#define LORA_NOALLOC_SCRATCH_BYTES (32u << 20)
+lora_status lora_bwd_noalloc(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                             const lora_bf16* S_saved, const lora_bf16* dY,
+                             int64_t M, int64_t K, int64_t N, int32_t r, float s, float p, uint64_t seed,
+                             lora_bf16* dX, float* dA, float* dB, int accumulate, lora_stream stream);
 
 /* Forward on a packed mixed-adapter batch (Section 5.1, FusedMultiLoRA): rows
  * [seg_offsets[g], seg_offsets[g+1]) use adapter g = (A[g], B[g], s[g], p[g], seeds[g]); the base

@@ -16,7 +16,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblorafusion_hip.so")
 
-EXPORTS = ("lora_fwd", "lora_bwd", "multi_lora_fwd", "multi_lora_bwd", "multi_lora_fwd_ranked",
+EXPORTS = ("lora_fwd", "lora_bwd", "lora_bwd_noalloc", "multi_lora_fwd", "multi_lora_bwd", "multi_lora_fwd_ranked",
            "multi_lora_bwd_ranked", "lora_bwd_workspace_bytes",
            "lora_debug_mask", "lora_status_string", "lora_version", "lora_set_row_tile", "lora_debug_stream_panels",
            "lora_unfused_fwd", "lora_unfused_bwd", "lora_unfused_workspace_bytes")
@@ -35,6 +35,8 @@ def load_library() -> C.CDLL:
     P, I64, I32, F, U64, SZ = C.c_void_p, C.c_int64, C.c_int32, C.c_float, C.c_uint64, C.c_size_t
     lib.lora_fwd.argtypes = [P, P, P, P, I64, I64, I64, I32, F, F, U64, P, P, P]
     lib.lora_bwd.argtypes = [P, P, P, P, P, P, I64, I64, I64, I32, F, F, U64, P, P, P, C.c_int, P, SZ, P]
+    lib.lora_bwd_noalloc.argtypes = [P, P, P, P, P, P, I64, I64, I64, I32, F, F, U64, P, P, P, C.c_int, P]
+    lib.lora_bwd_noalloc.restype = C.c_int
     lib.multi_lora_fwd.argtypes = [P, P, P, P, I64, I64, I64, I32, I32,
                                    C.POINTER(I64), C.POINTER(F), C.POINTER(F), C.POINTER(U64), P, P, P]
     lib.multi_lora_bwd.argtypes = [P, P, P, P, P, P, I64, I64, I64, I32, I32,
@@ -132,6 +134,19 @@ def lora_bwd(X, W, A, B, S, dY, s, p, seed, need_dx=True, dA=None, dB=None, accu
     ws = alloc_workspace(M, K, N, r, 1, X.device) if workspace is None else workspace
     _check(load_library().lora_bwd(_ptr(X), _ptr(W), _ptr(A), _ptr(B), _ptr(S), _ptr(dY), M, K, N, r, s, p, seed,
                                    _ptr(dX), _ptr(dA), _ptr(dB), int(accumulate), _ptr(ws), ws.numel(), _stream()))
+    return dX, dA, dB
+
+
+NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def lora_bwd_noalloc(X, W, A, B, S, dY, s, p, seed, dX, dA, dB, accumulate=False):
+    """lora_bwd on the library's built-in scratch: the caller passes every output (dX may be None), nothing
+    is allocated here or in the library."""
+    M, K = X.shape
+    N, r = B.shape
+    _check(load_library().lora_bwd_noalloc(_ptr(X), _ptr(W), _ptr(A), _ptr(B), _ptr(S), _ptr(dY), M, K, N, r, s, p, seed,
+                                           _ptr(dX), _ptr(dA), _ptr(dB), int(accumulate), _stream()))
     return dX, dA, dB
 
 

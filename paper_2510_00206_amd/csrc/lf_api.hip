@@ -4,6 +4,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "../../include/lorafusion.h"
@@ -148,6 +149,30 @@ lora_status bwd_impl(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A,
     return LORA_OK;
 }
 
+// ---- scratch of the allocation-free backward ------------------------------------------------------
+// One array per GPU, part of the library's device image: it exists from the moment the image is loaded
+// on a device until the process ends.  In host code `scratch` is only a handle for the symbol, never a
+// device address: the address of each device's copy is asked for once (with that device current) and
+// only that pointer is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[LORA_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];        // per device, filled on the first call on that device
+
+lora_status scratch_of_current_device(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LORA_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return LORA_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return LORA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -231,6 +256,35 @@ lora_status lora_bwd(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A,
                           workspace, workspace_bytes, stream);
 }
 
+lora_status lora_bwd_noalloc(const lora_bf16* X, const lora_bf16* W, const lora_bf16* A, const lora_bf16* B,
+                             const lora_bf16* S_saved, const lora_bf16* dY,
+                             int64_t M, int64_t K, int64_t N, int32_t r, float s, float p, uint64_t seed,
+                             lora_bf16* dX, float* dA, float* dB, int accumulate, lora_stream stream) {
+    if (!W || !A || !B || !dA || !dB) return LORA_ERR_NULL;
+    if (M != 0 && (!X || !S_saved || !dY)) return LORA_ERR_NULL;
+    lora_status st = check_shape(M, K, N, r, 1);
+    if (st != LORA_OK) return st;
+    if (misaligned(X) || misaligned(W) || misaligned(A) || misaligned(B) || misaligned(S_saved) ||
+        misaligned(dY) || misaligned(dA) || misaligned(dB) || (dX && misaligned(dX)))
+        return LORA_ERR_ALIGN;
+    const int64_t off[2] = {0, M};
+    AdapterTable tb;
+    st = build_table(tb, M, r, 1, off, &s, &p, &seed, nullptr);
+    if (st != LORA_OK) return st;
+    // exactly the planes this call's launches will write (their panel heights are known here)
+    const BwdPlan pl = plan_bwd(tb, K, N);
+    const int64_t planes_db = count_panels(tb, pl.rows_db), planes_da = count_panels(tb, pl.rows_da);
+    if (carve(nullptr, M, K, N, r, planes_db, planes_da).bytes > (size_t)LORA_NOALLOC_SCRATCH_BYTES)
+        return LORA_ERR_WORKSPACE;
+    void* base = nullptr;
+    st = scratch_of_current_device(&base);
+    if (st != LORA_OK) return st;
+    // Nothing in the scratch has to start at zero: every partial plane and every dS element that a
+    // later kernel of this call reads is written by an earlier kernel of this call.
+    return bwd_impl(X, W, A, B, S_saved, dY, M, K, N, r, tb, dX, dA, dB, accumulate,
+                    carve(base, M, K, N, r, planes_db, planes_da), pl, (hipStream_t)stream);
+}
+
 lora_status lora_debug_mask(int64_t M, int64_t K, float p, uint64_t seed, uint8_t* keep, lora_stream stream) {
     if (M < 0 || K < 0 || M >= (1ll << 31) || K >= (1ll << 31)) return LORA_ERR_SHAPE;
     AdapterTable tb;
@@ -269,7 +323,7 @@ const char* lora_status_string(lora_status st) {
         case LORA_ERR_ALIGN: return "pointer not sufficiently aligned";
         case LORA_ERR_PARAM: return "dropout probability outside [0,1) or non-finite scale";
         case LORA_ERR_SEGMENTS: return "segment offsets must rise from 0 to M";
-        case LORA_ERR_WORKSPACE: return "workspace too small";
+        case LORA_ERR_WORKSPACE: return "workspace too small (lora_bwd_noalloc: problem beyond the built-in scratch)";
         case LORA_ERR_UNSUPPORTED: return "unsupported size (K, N multiples of 64; r in {16,32,64}; G <= 64)";
         case LORA_ERR_HIP: return "kernel launch failed";
     }

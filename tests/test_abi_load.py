@@ -88,6 +88,20 @@ def test_host_side_validation_needs_no_gpu(lib):
               ok_ptr, ok_ptr, ok_ptr, 0, C.c_void_p(0x100000), need - 1, None) == 6
 
 
+def test_noalloc_backward_validates_on_the_host(lib):
+    """lora_bwd_noalloc refuses bad arguments and problems beyond its built-in scratch before it touches a GPU."""
+    ok = C.c_void_p(0x1000)
+    f = lib.lora_bwd_noalloc
+    f.argtypes = [C.c_void_p] * 6 + [C.c_int64] * 3 + [C.c_int32, C.c_float, C.c_float, C.c_uint64] + [C.c_void_p] * 3 + [C.c_int, C.c_void_p]
+    f.restype = C.c_int
+    assert f(ok, None, ok, ok, ok, ok, 256, 128, 128, 16, 1.0, 0.1, 1, ok, ok, ok, 0, None) == 1
+    assert f(ok, ok, ok, ok, ok, ok, 256, 100, 128, 16, 1.0, 0.1, 1, ok, ok, ok, 0, None) == 7
+    assert f(ok, ok, ok, ok, ok, ok, 256, 128, 128, 16, 1.0, 1.5, 1, ok, ok, ok, 0, None) == 4
+    assert f(ok, ok, ok, ok, ok, C.c_void_p(0x1004), 256, 128, 128, 16, 1.0, 0.1, 1, ok, ok, ok, 0, None) == 3
+    assert f(ok, ok, ok, ok, ok, ok, 16384, 8192, 8192, 64, 1.0, 0.1, 1, ok, ok, ok, 0, None) == 6
+    assert b"scratch" in lib.lora_status_string(6)
+
+
 def test_workspace_holds_every_panel_choice(lib):
     """Host logic: whatever row-panel height the streaming reductions pick (all three row-tile settings), the
     number of partial planes stays within what the workspace query provides for."""
