@@ -158,6 +158,16 @@ __device__ __forceinline__ void read_frags(Frags<MB>& f, const char* lds_tok, co
         f.ft[mi] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_tok + row_off_kk + mi * 4096));
 }
 
+// An MFMA under wave-uniform control flow, issued from assembly with the accumulator tied to itself: with
+// the builtin, the compiler may give the result another register block than its input and then pays for the
+// merge after the branch with copies of (and scratch space for) whole accumulator blocks.  The matrix pipe
+// interlocks a dependent MFMA on the same block by itself; what the compiler can no longer see is the
+// distance that any other reader of the block has to keep: mfma_in_place_done() supplies it after the last one.
+__device__ __forceinline__ void mfma_in_place(f32x16& c, bf16x8 a, bf16x8 b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_in_place_done() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+
 // MFMAs of all token-row blocks against all four output-column blocks.
 template <int MB>
 __device__ __forceinline__ void mma_frags(f32x16 (&acc)[MB][4], const Frags<MB>& f) {
@@ -203,16 +213,85 @@ __device__ __forceinline__ void read_frag_item(Frags<MB>& f, const char* lds_tok
     }
 }
 
+// ---- dropout keep flags formed in the shadow of the matrix work (operation (5)) ---------------------
+// Operation (5) needs keep(i, j) for every element of its output tile: 128 hash words per lane and
+// 256x256 tile.  The integer work is issued a few instructions at a time in MFMA slots that carry no
+// fragment read and no copy, where it runs while the matrix pipe is busy; each piece is one inline
+// assembly statement so that it stays in its slot.  A slab step forms WPS words (4 in a 256-row tile,
+// 2 in a 128-row tile), i.e. the flags of a tile are complete after 32 slab steps; sixteen words (32
+// elements: the low halves in bits 0..15, the high halves in bits 16..31) fill one flag register, which
+// is then parked in LDS until the epilogue.
+// Lane l of a wave owns, in 32x32 block (mi, ni), the elements 4*g4 + 2*pr + {0, 1} (g4 = 0..3, pr = 0..1) =
+// columns ni*32 + 8*g4 + 4*(l>>5) + 2*pr + {0, 1}: column pair cp0 + ni*16 + 4*g4 + pr with cp0 the lane's
+// first pair.  Word number wd = mi*32 + ni*8 + g4*2 + pr; flag register wd >> 4, bit wd & 15 (+16).
+struct KeepShadow {
+    uint32_t xb, x, t, m4, fcur;     // vector registers: running hash state, flags of the current register
+    uint32_t x0, rkb;                // row keys of the current 32-row block: rk.a + cp0 * kGold, rk.b
+    uint32_t xoff, shift, tm1;       // wave-uniform: pair offset * kGold and flag position of this step; packed T-1
+};
+struct NoShadow {};
+
+// Piece PID of a slab step: word J = PID >> 2, stage PID & 3 of
+//   x = x0 + pair*kGold;  x ^= x>>16;  | x *= M1; x += rk.b;  | x ^= x>>15; x *= M2;  | x ^= x>>16; flags
+template <int WPS, int PID>
+__device__ __forceinline__ void keep_piece(KeepShadow& k) {
+    constexpr int J = PID >> 2, ST = PID & 3;
+    constexpr uint32_t CJ = (uint32_t)((J >> 1) * 4 + (J & 1)) * kGold;      // pairs 0, 1, 4, 5 past the step's first
+    if constexpr (ST == 0 && J == 0) {
+        asm volatile("v_add_u32 %0, %4, %3\n\tv_lshrrev_b32 %1, 16, %0\n\tv_xor_b32 %2, %0, %1"
+                     : "=&v"(k.xb), "=&v"(k.t), "=&v"(k.x) : "v"(k.x0), "s"(k.xoff));
+    } else if constexpr (ST == 0) {
+        asm volatile("v_add_u32 %0, %3, %2\n\tv_lshrrev_b32 %1, 16, %0\n\tv_xor_b32 %0, %0, %1"
+                     : "=&v"(k.x), "=&v"(k.t) : "v"(k.xb), "s"(CJ));
+    } else if constexpr (ST == 1) {
+        asm volatile("v_mul_lo_u32 %0, %0, %2\n\tv_add_u32 %0, %0, %1" : "+v"(k.x) : "v"(k.rkb), "s"(kM1));
+    } else if constexpr (ST == 2) {
+        asm volatile("v_lshrrev_b32 %1, 15, %0\n\tv_xor_b32 %0, %0, %1\n\tv_mul_lo_u32 %0, %0, %2"
+                     : "+v"(k.x), "=&v"(k.t) : "s"(kM2));
+    } else {
+        // keep flag of a 16-bit half: min(saturating(bits - (T-1)), 1), both halves at once
+        if constexpr (J == 0)
+            asm volatile("v_lshrrev_b32 %1, 16, %0\n\tv_xor_b32 %0, %0, %1\n\tv_pk_sub_u16 %1, %0, %3 clamp\n\t"
+                         "v_pk_min_u16 %2, %1, %4"
+                         : "+v"(k.x), "=&v"(k.t), "=&v"(k.m4) : "s"(k.tm1), "s"(0x00010001u));
+        else
+            asm volatile("v_lshrrev_b32 %1, 16, %0\n\tv_xor_b32 %0, %0, %1\n\tv_pk_sub_u16 %1, %0, %3 clamp\n\t"
+                         "v_pk_min_u16 %1, %1, %4\n\tv_lshl_or_b32 %2, %1, %5, %2"
+                         : "+v"(k.x), "=&v"(k.t), "+v"(k.m4) : "s"(k.tm1), "s"(0x00010001u), "n"(J));
+        if constexpr (J == WPS - 1)
+            asm volatile("v_lshl_or_b32 %0, %1, %2, %0" : "+v"(k.fcur) : "v"(k.m4), "s"(k.shift));
+    }
+}
+
+// Which piece rides on MFMA slot S of sub-step SUB (-1: none): slots without a fragment read or a copy.
+constexpr int shadow_piece_of(int MB, int SUB, int S) {
+    if (MB == 4) return SUB == 2 && (S & 1) ? S >> 1 : SUB == 3 && S < 8 ? 8 + S : -1;
+    return SUB < 3 && S == 6 ? SUB : SUB == 3 && S < 4 ? 3 + S : SUB == 3 && S == 7 ? 7 : -1;
+}
+template <int MB, int SUB, int S> __device__ __forceinline__ void shadow_slot(NoShadow&) {}
+template <int MB, int SUB, int S> __device__ __forceinline__ void shadow_slot(KeepShadow& k) {
+    constexpr int pid = shadow_piece_of(MB, SUB, S);
+    if constexpr (pid >= 0) keep_piece<(MB == 4 ? 4 : 2), pid>(k);
+}
+// the same pieces outside any slab step (tiles with fewer than 32 slab steps)
+template <int WPS, int PID = 0>
+__device__ __forceinline__ void keep_pieces_plain(KeepShadow& k) {
+    if constexpr (PID < 4 * WPS) {
+        keep_piece<WPS, PID>(k);
+        keep_pieces_plain<WPS, PID + 1>(k);
+    }
+}
+
 // One sub-step: 4*MB MFMAs, each followed by at most one other instruction group (two in the 128-row
 // variant) - fragment reads of the next sub-step and global->LDS copies of the next slab pair - so that
 // every LDS read and every copy is issued while an MFMA executes (a copy or read issued between two
 // groups of MFMAs leaves the matrix pipe idle for its whole issue time).  With MB = 4 reads sit on
 // even slots and copies on odd ones; with MB = 2 the six reads sit on slots 0..5 and copies on odd slots.
 // MODE 0: reads of sub-step KK_NEXT + copies; MODE 1: MFMAs only; MODE 2: reads of the next slab's sub-step 0.
-template <bool OUT_IS_COL_SLAB, int MB, int KK_NEXT, int COPY0, int COPIES, int SLOT0, int SLOT1, int MODE>
+template <bool OUT_IS_COL_SLAB, int MB, int SUB, int KK_NEXT, int COPY0, int COPIES, int SLOT0, int SLOT1, int MODE, class SH>
 __device__ __forceinline__ void phase_slots(f32x16 (&acc)[MB][4], const Frags<MB>& cur, Frags<MB>& nxt,
                                             const char* lds_tok, const char* lds_out, const FragLanes& fl,
-                                            const NextSlabs& nx) {
+                                            const NextSlabs& nx, SH& sh) {
 #define LF_SLOT(S)                                                                                        \
     if constexpr ((S) >= SLOT0 && (S) < SLOT1 && (S) < 4 * MB) {                                         \
         acc[(S) >> 2][(S) & 3] = LF_MFMA(cur.fo[(S) & 3], cur.ft[(S) >> 2], acc[(S) >> 2][(S) & 3]);      \
@@ -237,6 +316,7 @@ __device__ __forceinline__ void phase_slots(f32x16 (&acc)[MB][4], const Frags<MB
             if constexpr (((S) & 1) == 1 && ((S) >> 1) < COPIES)                                          \
                 issue_copy<MB, (COPY0 + ((S) >> 1))>(nx);                                                   \
         }                                                                                                 \
+        shadow_slot<MB, SUB, (S)>(sh);                                                                    \
         __builtin_amdgcn_sched_barrier(0);                                                                \
     }
     LF_SLOT(0) LF_SLOT(1) LF_SLOT(2) LF_SLOT(3) LF_SLOT(4) LF_SLOT(5) LF_SLOT(6) LF_SLOT(7)
@@ -248,27 +328,27 @@ __device__ __forceinline__ void phase_slots(f32x16 (&acc)[MB][4], const Frags<MB
 // 0 and 1; 12 over sub-steps 0..2 in the 128-row variant), and in the middle of sub-step 3 the hand-over
 // (copies landed, workgroup barrier) followed by the first fragment reads of the next slab.  On entry
 // f0 holds the fragments of sub-step 0 of the current slab; on exit it holds those of the next slab.
-template <bool OUT_IS_COL_SLAB, int MB>
+template <bool OUT_IS_COL_SLAB, int MB, class SH>
 __device__ __forceinline__ void slab_step(f32x16 (&acc)[MB][4], Frags<MB>& f0, Frags<MB>& f1, const char* cur_tok,
                                           const char* cur_out, const char* nxt_tok, const char* nxt_out,
-                                          const FragLanes& fl, const NextSlabs& nx) {
+                                          const FragLanes& fl, const NextSlabs& nx, SH& sh) {
     static_assert(PASSES == 8 && (MB == 4 || MB == 2), "copy schedule below assumes 8 + 2*MB copies per slab pair");
     constexpr int NS = 4 * MB;
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (MB == 4) {
-        phase_slots<OUT_IS_COL_SLAB, MB, 1, 0, 8, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx);   // copies 0..7
-        phase_slots<OUT_IS_COL_SLAB, MB, 2, 8, 8, 0, NS, 0>(acc, f1, f0, cur_tok, cur_out, fl, nx);   // copies 8..15
-        phase_slots<OUT_IS_COL_SLAB, MB, 3, 0, 0, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx);
+        phase_slots<OUT_IS_COL_SLAB, MB, 0, 1, 0, 8, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh);   // copies 0..7
+        phase_slots<OUT_IS_COL_SLAB, MB, 1, 2, 8, 8, 0, NS, 0>(acc, f1, f0, cur_tok, cur_out, fl, nx, sh);   // copies 8..15
+        phase_slots<OUT_IS_COL_SLAB, MB, 2, 3, 0, 0, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh);
     } else {
-        phase_slots<OUT_IS_COL_SLAB, MB, 1, 0, 4, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx);   // copies 0..3
-        phase_slots<OUT_IS_COL_SLAB, MB, 2, 4, 4, 0, NS, 0>(acc, f1, f0, cur_tok, cur_out, fl, nx);   // copies 4..7
-        phase_slots<OUT_IS_COL_SLAB, MB, 3, 8, 4, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx);   // copies 8..11
+        phase_slots<OUT_IS_COL_SLAB, MB, 0, 1, 0, 4, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh);   // copies 0..3
+        phase_slots<OUT_IS_COL_SLAB, MB, 1, 2, 4, 4, 0, NS, 0>(acc, f1, f0, cur_tok, cur_out, fl, nx, sh);   // copies 4..7
+        phase_slots<OUT_IS_COL_SLAB, MB, 2, 3, 8, 4, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh);   // copies 8..11
     }
     // sub-step 3: first half, hand-over, second half with the next slab's first fragment reads
-    phase_slots<OUT_IS_COL_SLAB, MB, 0, 0, 0, 0, NS / 2, 1>(acc, f1, f0, cur_tok, cur_out, fl, nx);
+    phase_slots<OUT_IS_COL_SLAB, MB, 3, 0, 0, 0, 0, NS / 2, 1>(acc, f1, f0, cur_tok, cur_out, fl, nx, sh);
     wait_slab_loads();
     __syncthreads();
-    phase_slots<OUT_IS_COL_SLAB, MB, 0, 0, 0, NS / 2, NS, 2>(acc, f1, f0, nxt_tok, nxt_out, fl, nx);
+    phase_slots<OUT_IS_COL_SLAB, MB, 3, 0, 0, 0, NS / 2, NS, 2>(acc, f1, f0, nxt_tok, nxt_out, fl, nx, sh);
 }
 
 // Accumulator element (mi, ni, i) of lane l is output row  wm*32*MB + mi*32 + (l & 31)  and output
@@ -371,13 +451,13 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     const bool has_lora = p.r > 0;
     const int rr = has_lora ? p.r : 16;
     const SlabLanes sx = row_slab_lanes(p.K, rt.rows, 8), sw = row_slab_lanes(p.K, cols_valid, 8);
-    const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
     const lora_bf16* Ssrc = p.S + (int64_t)rt.row_start * p.r;
     const lora_bf16* Bsrc = p.B + ((int64_t)rt.g * p.N + n0) * p.r;
     if (nk > 0) {
         load_slab<2 * MB>(lds0, Xt, sx);
         load_slab(lds0 + TILE_BYTES, Wt, sw);
     } else {
+        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
         load_slab<2 * MB>(lds0, Ssrc, ss);
         load_slab(lds0 + TILE_BYTES, Bsrc, sb);
     }
@@ -385,6 +465,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     wait_slab_loads();
     __syncthreads();
     Frags<MB> f0, f1;
+    NoShadow none;
     read_frags<false>(f0, smem + tok_org, smem + out_org, fl, fl.row_off[0], 0);
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
     for (int kt = 0; kt + 1 < nk; ++kt) {
@@ -392,8 +473,11 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
         const NextSlabs nx{(const char*)(Xt + (kt + 1) * BK), (const char*)(Wt + (kt + 1) * BK), sx, sw,
                            lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, true};
         slab_step<false, MB>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
-                         smem + nxt + out_org, fl, nx);
+                         smem + nxt + out_org, fl, nx, none);
     }
+    // the lane offsets of the LoRA slab pair are formed only now: through the main loop they would cost
+    // sixteen registers that it does not have
+    const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
     if (nk > 0) {
         // after the last base slab the LoRA step rides as one more slab: token operand S' [rows, r],
         // out operand B [N, r]
@@ -401,36 +485,28 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
         const NextSlabs nx{(const char*)Ssrc, (const char*)Bsrc, ss, sb,
                            lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, has_lora && !gm.mixed};
         slab_step<false, MB>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
-                         smem + nxt + out_org, fl, nx);
+                         smem + nxt + out_org, fl, nx, none);
     }
-    if (has_lora && !gm.mixed) {
-        const int lo = (nk & 1) * STAGE_BYTES;         // the stage that holds the LoRA slab
-        const int nkk = p.tb.rank[rt.g] >> 4;
-        mma_frags(acc, f0);
+    if (has_lora) {
+        // One pass per adapter present in the tile: a single one unless the tile is mixed (FusedMultiLoRA
+        // with tiles cut uniformly over the packed batch: one adapter per 64-row group).  The slab pair of
+        // an unmixed tile has come in with the last base slab; a mixed tile loads the S' slab of the whole
+        // tile once and the B slab once per group.  A group's sub-steps go only to the 32-row blocks inside
+        // it, so that no value of one adapter ever meets a row of another - not even multiplied by zero.
+        const int lo = (nk & 1) * STAGE_BYTES;         // the stage that holds the LoRA slab pair
         const int l = threadIdx.x & 63;
+        const int ngroups = gm.mixed ? (rt.rows + 63) >> 6 : 1;
 #pragma unroll 1
-        for (int kk = 1; kk < nkk; ++kk) {
-            Frags<MB> f;
-            read_frags<false>(f, smem + lo + tok_org, smem + lo + out_org, fl, row_slab_off(l & 31, 2 * kk + (l >> 5)), 0);
-            mma_frags(acc, f);
-        }
-    } else if (has_lora) {
-        // A tile that holds several adapters (FusedMultiLoRA with tiles cut uniformly over the packed
-        // batch): one run of 64-row groups per adapter.  The S' slab of the whole tile is loaded once, the
-        // B slab once per run, and a run's sub-steps go only to the 32-row blocks inside it, so that no
-        // value of one adapter ever meets a row of another - not even multiplied by zero.
-        const int lo = (nk & 1) * STAGE_BYTES;
-        const int l = threadIdx.x & 63;
-        const int nq = (rt.rows + 63) >> 6;
-        for (int q = 0; q < nq;) {
+        for (int q = 0; q < ngroups; ++q) {
             const int g = group_adapter(gm, q);
-            int qe = q + 1;
-            while (qe < nq && group_adapter(gm, qe) == g) ++qe;
-            __syncthreads();                           // every wave is done with the stage's previous contents
-            if (q == 0) load_slab<2 * MB>(lds0 + lo, Ssrc, ss);
-            load_slab(lds0 + lo + TILE_BYTES, p.B + ((int64_t)g * p.N + n0) * p.r, sb);
-            wait_slab_loads();
-            __syncthreads();
+            if (gm.mixed) {
+                __syncthreads();                       // every wave is done with the stage's previous contents
+                if (q == 0) load_slab<2 * MB>(lds0 + lo, Ssrc, ss);
+                load_slab(lds0 + lo + TILE_BYTES, p.B + ((int64_t)g * p.N + n0) * p.r, sb);
+                wait_slab_loads();
+                __syncthreads();
+            }
+            const int blk_lo = gm.mixed ? 64 * q : 0, blk_hi = gm.mixed ? 64 * q + 64 : BM;
             const int nkk = p.tb.rank[g] >> 4;
 #pragma unroll 1
             for (int kk = 0; kk < nkk; ++kk) {
@@ -439,21 +515,85 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
 #pragma unroll
                 for (int mi = 0; mi < MB; ++mi) {
                     const int blk = wm * (32 * MB) + mi * 32;           // first tile row of the block
-                    if (blk < 64 * q || blk >= 64 * qe) continue;
+                    if (blk < blk_lo || blk >= blk_hi) continue;
 #pragma unroll
-                    for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = LF_MFMA(f.fo[ni], f.ft[mi], acc[mi][ni]);
+                    for (int ni = 0; ni < 4; ++ni) mfma_in_place(acc[mi][ni], f.fo[ni], f.ft[mi]);
                 }
             }
-            q = qe;
         }
+        mfma_in_place_done();
     }
     store_tile(acc, p.Y, p.N, rt.row_start, rt.rows, n0, cols_valid, wm, wn, smem);
 }
 
 // ---- operation (5): dX = dY W^T + mask*q*(dS A^T) ------------------------------------------------
+// The LoRA term of one 32-row block of a wave's sub-tile, added to the finished base-gradient
+// accumulators, rounded to bf16 and written out: t = dS A^T on a fresh accumulator per 32x32 block
+// (dS arrives scaled by s*q), t & flag, + acc, pack; the block's 32 x 128 bf16 go through 8 KB of LDS of
+// the wave's own (`stage`) so that whole 256-byte row segments are stored.  lds_tok / lds_out: the
+// LoRA slab pair (dS rows of this wave, A columns of this wave).  F0 / F1: keep flags of blocks
+// (mi, 0..1) / (mi, 2..3), bit (ni & 1) * 8 + g4 * 2 + pr for element 4*g4 + 2*pr, +16 for the next one.
 template <int MB>
+__device__ __forceinline__ void lora_block_store(f32x16 (&acc)[4], int mi, const char* lds_tok, const char* lds_out,
+                                                 const FragLanes& fl, int nkk, uint32_t F0, uint32_t F1, char* stage,
+                                                 lora_bf16* out, int64_t ld, int row0_glob, int rows_left, bool col_ok,
+                                                 int l) {
+    const int r = l & 31;
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) {
+        f32x16 t;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) t[i] = 0.f;
+#pragma unroll 1
+        for (int kk = 0; kk < nkk; ++kk) {
+            const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni][0] + kk * 8192);
+            const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni][1] + kk * 8192);
+            const bf16x8 ft = __builtin_bit_cast(
+                bf16x8, *(const u32x4*)(lds_tok + row_slab_off(l & 31, 2 * kk + (l >> 5)) + mi * 4096));
+            t = LF_MFMA(join_tr(lo, hi), ft, t);
+        }
+        asm volatile("" : "+v"(t));                  // in vector registers, where the masking below reads it
+        asm volatile("" : "+a"(acc[ni]));            // ... and the block stays an accumulator block up to here
+        const uint32_t F = ni < 2 ? F0 : F1;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+            float v[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int bit = (ni & 1) * 8 + g4 * 2 + (e >> 1) + (e & 1) * 16;
+                const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe((int)F, bit, 1);     // 0 or 0xFFFFFFFF
+                const float te = t[4 * g4 + e];      // (a copy: bit_cast of a vector element reads element 0)
+                v[e] = acc[ni][4 * g4 + e] + __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, te) & m);
+            }
+            u32x2 o;
+            o.x = pack_bf16x2(v[0], v[1]);
+            o.y = pack_bf16x2(v[2], v[3]);
+            const int slot = ni * 8 + 2 * g4 + (l >> 5);
+            *(u32x2*)(stage + r * 256 + ((slot ^ r) << 3)) = o;
+        }
+    }
+    // LDS operations of one wave complete in order: the reads below see the writes above, and the next
+    // block's writes come after these reads
+    const int j = l & 15;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+        const int rr = it * 4 + (l >> 4);
+        u32x4 v = *(const u32x4*)(stage + rr * 256 + ((j ^ (rr >> 1)) << 4));
+        if (rr & 1) v = u32x4{v.z, v.w, v.x, v.y};
+        if (col_ok && rr < rows_left)
+            __builtin_nontemporal_store(v, (u32x4*)(out + (int64_t)(row0_glob + rr) * ld + j * 8));
+    }
+}
+
+// LORA = false: the plain product dX = dY W^T (frozen linear, unfused baseline).  LORA = true: the base
+// product first, while the keep flags of the tile are formed in the shadow of its MFMAs; the LoRA slab
+// pair [dS | A] rides in as one more slab during the last base slab, and the masked LoRA term is added
+// block by block on the way out.  p.N == 0 (LoRA term only) serves the unfused baseline.
+template <int MB, bool LORA>
 __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     constexpr int BM = 64 * MB;
+    constexpr int WPS = MB == 4 ? 4 : 2;             // hash words per slab step and lane
+    constexpr int FLAG_STEPS = 32 * MB / WPS;        // slab steps until the tile's flags are complete: 32
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int tm, tn;
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
@@ -468,7 +608,8 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     }
     const int j0 = tn * BN;                          // output columns are input features
     const int cols_valid = min(BN, p.K - j0);
-    const int w = threadIdx.x >> 6, wm = w & 1, wn = w >> 1;
+    const int l = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wm = w & 1, wn = w >> 1;
 
     f32x16 acc[MB][4];
 
@@ -478,32 +619,120 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     const FragLanes fl = frag_lanes();
     const int tok_org = wm * (32 * MB) * 128, out_org = TILE_BYTES + wn * 128 * 2;
     const SlabLanes sd = row_slab_lanes(p.N, rt.rows, 8), sw = col_slab_lanes(p.K, BK, cols_valid);
-
-    // LoRA step first: acc = dS A^T (dS arrives scaled by s*q), then the mask is applied to the accumulators and the
-    // base-gradient contraction continues on top of them.
-    // p.r == 0 (no LoRA term) and p.N == 0 (LoRA term only) serve the unfused baseline's plain GEMMs.
     const int nk = p.N / BK;
-    const SlabLanes ss = row_slab_lanes(p.r > 0 ? p.r : 16, rt.rows, p.r > 0 ? p.r >> 3 : 2);
-    const SlabLanes sa = col_slab_lanes(p.K, p.r > 0 ? p.r : 16, cols_valid);
-    if (p.r > 0) {
-        load_slab<2 * MB>(lds0 + STAGE_BYTES, p.dS + (int64_t)rt.row_start * p.r, ss);
-        load_slab(lds0 + STAGE_BYTES + TILE_BYTES, p.A + (int64_t)gm.g[0] * p.r * p.K + j0, sa);
-    }
+    const int rr = LORA ? p.r : 16;
+    const lora_bf16* dSt = p.dS + (int64_t)rt.row_start * rr;
+    const lora_bf16* At = p.A + (int64_t)gm.g[0] * rr * p.K + j0;         // A of the tile's first adapter
+    const int lo = (nk & 1) * STAGE_BYTES;           // the stage that receives the LoRA slab pair
     if (nk > 0) {
         load_slab<2 * MB>(lds0, dYt + 0, sd);
         load_slab(lds0 + TILE_BYTES, Wt, sw);
+    } else if (LORA) {
+        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sa = col_slab_lanes(p.K, rr, cols_valid);
+        load_slab<2 * MB>(lds0, dSt, ss);
+        load_slab(lds0 + TILE_BYTES, At, sa);
     }
     zero_acc(acc);                                     // while the first slabs are on their way
+
+    // keep flags: state of the hash pieces, and what changes with the 32-row block they work on
+    KeepShadow ks;
+    NoShadow none;
+    uint32_t keep_all = 0;
+    uint32_t* flags = (uint32_t*)(smem + GEMM_LDS_BYTES) + threadIdx.x;     // [2 * MB][NTHREADS]
+    const uint32_t cp0 = (uint32_t)(j0 + wn * 128 + 4 * (l >> 5)) >> 1;     // this lane's first column pair
+    auto keep_step_begin = [&](int kt) {
+        const int wd0 = kt * WPS, idx = wd0 & 31;
+        if (idx == 0) {
+            // next 32-row block of the wave: its adapter's threshold and the row keys of its rows
+            const int blk = wm * (32 * MB) + (wd0 >> 5) * 32;
+            const int g = group_adapter(gm, blk >> 6);
+            const KeepThreshold kth = keep_threshold(p.tb.T[g]);
+            ks.tm1 = kth.tm1_packed;
+            keep_all = kth.keep_all;
+            const RowKey rk = row_key(p.tb.k0[g], p.tb.k1[g], (uint32_t)(rt.row_start - p.tb.row0[g] + blk + (l & 31)));
+            ks.x0 = rk.a + cp0 * kGold;
+            ks.rkb = rk.b;
+        }
+        ks.xoff = (uint32_t)((idx >> 3) * 16 + ((idx >> 1) & 3) * 4) * kGold;
+        ks.shift = (uint32_t)(wd0 & 15);
+    };
+    auto keep_step_end = [&](int kt) {
+        const int wd0 = kt * WPS;
+        if ((wd0 & 15) + WPS == 16) {
+            flags[(wd0 >> 4) * NTHREADS] = ks.fcur | keep_all;
+            ks.fcur = 0;
+        }
+    };
+    if (LORA) {
+        // defined from the start: the pieces also run in a step that forms nothing (see the last base slab)
+        ks.fcur = ks.x0 = ks.rkb = ks.xoff = ks.shift = ks.tm1 = 0;
+    }
+
     wait_slab_loads();
     __syncthreads();
-    if (p.r > 0) {
-        // One run of 64-row groups per adapter present in the tile (a single run unless the tile is
-        // mixed).  Within a run, one 32x32 block at a time: t = dS A^T on a fresh accumulator, masked,
-        // becomes the block's starting value.
-        const int l = threadIdx.x & 63;
-        const char* lds_tok = smem + STAGE_BYTES + tok_org;
-        const char* lds_out = smem + STAGE_BYTES + out_org;
-        const uint32_t cp0 = (uint32_t)(j0 + wn * 128 + 4 * (l >> 5)) >> 1;     // this lane's first column pair
+    Frags<MB> f0, f1;
+    if (nk > 0) read_frags<true>(f0, smem + tok_org, smem + out_org, fl, fl.row_off[0], 0);
+    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
+    // slab steps 0 .. nk-2 bring the next base slab pair; the first 32 of all steps also carry the hash pieces
+    auto base_step = [&](int kt, auto& shadow) {
+        const int cur = (kt & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
+        const NextSlabs nx{(const char*)(dYt + (kt + 1) * BK), (const char*)(Wt + (int64_t)(kt + 1) * BK * p.K), sd, sw,
+                           lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, true};
+        slab_step<true, MB>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
+                            smem + nxt + out_org, fl, nx, shadow);
+    };
+    int kt = 0;
+    if constexpr (LORA) {
+        for (; kt < min(nk - 1, FLAG_STEPS); ++kt) {
+            keep_step_begin(kt);
+            base_step(kt, ks);
+            keep_step_end(kt);
+        }
+    }
+    for (; kt < nk - 1; ++kt) base_step(kt, none);
+    if (nk > 0) {
+        // the last base slab: the LoRA slab pair [dS | A] rides in as one more slab (nothing if there is no
+        // LoRA term); its lane offsets are formed only now, the main loop has no registers for them
+        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sa = col_slab_lanes(p.K, rr, cols_valid);
+        const int cur = (kt & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
+        const NextSlabs nx{(const char*)dSt, (const char*)At, ss, sa,
+                           lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, LORA};
+        if constexpr (LORA) {
+            // one code path for this step whatever kt is (two would have to merge all the accumulators):
+            // past the 32nd step the hash pieces still run, on a step number that is never flushed
+            const bool forming = kt < FLAG_STEPS;
+            if (forming) keep_step_begin(kt);
+            slab_step<true, MB>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
+                                smem + nxt + out_org, fl, nx, ks);
+            if (forming) keep_step_end(kt);
+        } else {
+            slab_step<true, MB>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
+                                smem + nxt + out_org, fl, nx, none);
+        }
+    }
+    if constexpr (!LORA) {
+        store_tile(acc, p.dX, p.K, rt.row_start, rt.rows, j0, cols_valid, wm, wn, smem);
+    } else {
+        // a contraction of fewer than 32 slabs has left flags to form: same pieces, on their own
+#pragma unroll 1
+        for (int kt = min(nk, FLAG_STEPS); kt < FLAG_STEPS; ++kt) {
+            keep_step_begin(kt);
+            keep_pieces_plain<WPS>(ks);
+            keep_step_end(kt);
+        }
+        __syncthreads();                              // every wave is done with the last base slab's stage
+        // The lane number is taken afresh and hidden from the optimiser: everything the way out derives from
+        // it (addresses, predicates) is then formed here instead of before the main loop, where it would
+        // occupy registers through all of it.
+        int le = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        asm volatile("" : "+v"(le));
+        const uint32_t* flags_e = (const uint32_t*)(smem + GEMM_LDS_BYTES) + w * 64 + le;
+        // One run of 64-row groups per adapter present in the tile (a single run unless the tile is mixed).
+        char* stage = smem + (STAGE_BYTES - lo) + w * 8192;
+        const char* lds_tok = smem + lo + tok_org;
+        const char* lds_out = smem + lo + out_org;
+        const bool col_ok = wn * 128 + (le & 15) * 8 < cols_valid;
+        lora_bf16* out = p.dX + (int64_t)rt.row_start * p.K + j0 + wn * 128;
         const int nq = (rt.rows + 63) >> 6;
         for (int q = 0; q < nq;) {
             const int g = group_adapter(gm, q);
@@ -511,63 +740,22 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
             while (qe < nq && group_adapter(gm, qe) == g) ++qe;
             if (q > 0) {                               // next adapter of a mixed tile: bring its A slab
                 __syncthreads();
-                load_slab(lds0 + STAGE_BYTES + TILE_BYTES, p.A + (int64_t)g * p.r * p.K + j0, sa);
+                const SlabLanes sa = col_slab_lanes(p.K, rr, cols_valid);
+                load_slab(lds0 + lo + TILE_BYTES, p.A + (int64_t)g * rr * p.K + j0, sa);
                 wait_slab_loads();
                 __syncthreads();
             }
-            const uint32_t T = p.tb.T[g];
             const int nkk = p.tb.rank[g] >> 4;
-            const uint32_t k0 = p.tb.k0[g], k1 = p.tb.k1[g];
-            const int lrow0 = rt.row_start - p.tb.row0[g];        // tile row -> row inside the adapter's segment
 #pragma unroll
             for (int mi = 0; mi < MB; ++mi) {
-                const int row = wm * (32 * MB) + mi * 32 + (l & 31);
-                if (wm * (32 * MB) + mi * 32 < 64 * q || wm * (32 * MB) + mi * 32 >= 64 * qe) continue;
-                const RowKey rk = row_key(k0, k1, (uint32_t)(lrow0 + row));
-                const uint32_t x0 = rk.a + cp0 * kGold;
-#pragma unroll
-                for (int ni = 0; ni < 4; ++ni) {
-                    f32x16 t;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) t[i] = 0.f;
-#pragma unroll 1
-                    for (int kk = 0; kk < nkk; ++kk) {
-                        const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni][0] + kk * 8192);
-                        const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni][1] + kk * 8192);
-                        const bf16x8 ft = __builtin_bit_cast(
-                            bf16x8, *(const u32x4*)(lds_tok + row_slab_off(l & 31, 2 * kk + (l >> 5)) + mi * 4096));
-                        t = LF_MFMA(join_tr(lo, hi), ft, t);
-                    }
-                    asm volatile("" : "+v"(t));              // in vector registers, where the selects below read it
-#pragma unroll
-                    for (int g4 = 0; g4 < 4; ++g4) {
-                        // columns ni*32 + 8*g4 + {0..3} past the lane's first column: pairs (ni*16 + 4*g4) + {0, 1}
-                        const uint32_t w0 = hash_word_at(rk, x0 + (uint32_t)(ni * 16 + 4 * g4) * kGold);
-                        const uint32_t w1 = hash_word_at(rk, x0 + (uint32_t)(ni * 16 + 4 * g4 + 1) * kGold);
-                        f32x16& a = acc[mi][ni];
-                        a[4 * g4 + 0] = (w0 & 0xFFFFu) >= T ? t[4 * g4 + 0] : 0.f;
-                        a[4 * g4 + 1] = (w0 >> 16) >= T ? t[4 * g4 + 1] : 0.f;
-                        a[4 * g4 + 2] = (w1 & 0xFFFFu) >= T ? t[4 * g4 + 2] : 0.f;
-                        a[4 * g4 + 3] = (w1 >> 16) >= T ? t[4 * g4 + 3] : 0.f;
-                    }
-                    asm volatile("" : "+a"(acc[mi][ni]));    // the block is final here: nothing sinks past
-                }
+                const int blk = wm * (32 * MB) + mi * 32;          // first tile row of the block
+                if (blk < 64 * q || blk >= 64 * qe) continue;
+                lora_block_store<MB>(acc[mi], mi, lds_tok, lds_out, fl, nkk, flags_e[(2 * mi) * NTHREADS],
+                                     flags_e[(2 * mi + 1) * NTHREADS], stage, out, p.K, blk, rt.rows - blk, col_ok, le);
             }
             q = qe;
         }
     }
-    __syncthreads();                                  // every wave is done with the LoRA slab in stage 1
-    Frags<MB> f0, f1;
-    if (nk > 0) read_frags<true>(f0, smem + tok_org, smem + out_org, fl, fl.row_off[0], 0);
-    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = (kt & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
-        const NextSlabs nx{(const char*)(dYt + (kt + 1) * BK), (const char*)(Wt + (int64_t)(kt + 1) * BK * p.K), sd, sw,
-                           lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, kt + 1 < nk};
-        slab_step<true, MB>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
-                        smem + nxt + out_org, fl, nx);
-    }
-    store_tile(acc, p.dX, p.K, rt.row_start, rt.rows, j0, cols_valid, wm, wn, smem);
 }
 
 // ---- host launchers -------------------------------------------------------------------------------
@@ -611,13 +799,13 @@ static RowTiling plan_row_tiles(const AdapterTable& tb, int M, int tiles_n, int 
 }
 
 template <typename K, typename A>
-static hipError_t launch_gemm(K kernel, bool& attr_set, const A& a, hipStream_t st) {
+static hipError_t launch_gemm(K kernel, bool& attr_set, const A& a, hipStream_t st, int lds_bytes = GEMM_LDS_BYTES) {
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kernel, dim3(a.tiles_m * a.tiles_n), dim3(NTHREADS), GEMM_LDS_BYTES, st, a);
+    hipLaunchKernelGGL(kernel, dim3(a.tiles_m * a.tiles_n), dim3(NTHREADS), lds_bytes, st, a);
     return hipGetLastError();
 }
 
@@ -638,9 +826,13 @@ hipError_t launch_bwd_dx(DxGemmArgs a, int forced, hipStream_t st) {
     a.uniform_tiles = t.uniform;
     a.tiles_m = t.tiles_m;
     if (a.tiles_m == 0) return hipSuccess;
-    static bool attr_set[2] = {false, false};
-    return t.bm == 256 ? launch_gemm(bwd_dx_kernel<4>, attr_set[0], a, st)
-                       : launch_gemm(bwd_dx_kernel<2>, attr_set[1], a, st);
+    static bool attr_set[4] = {false, false, false, false};
+    // with a LoRA term: the slab stages plus the parked keep flags (2 * MB words per lane)
+    if (a.r > 0)
+        return t.bm == 256 ? launch_gemm(bwd_dx_kernel<4, true>, attr_set[0], a, st, GEMM_LDS_BYTES + 8 * NTHREADS * 4)
+                           : launch_gemm(bwd_dx_kernel<2, true>, attr_set[1], a, st, GEMM_LDS_BYTES + 4 * NTHREADS * 4);
+    return t.bm == 256 ? launch_gemm(bwd_dx_kernel<4, false>, attr_set[2], a, st)
+                       : launch_gemm(bwd_dx_kernel<2, false>, attr_set[3], a, st);
 }
 
 }  // namespace lf
