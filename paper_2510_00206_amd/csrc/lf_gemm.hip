@@ -541,18 +541,22 @@ __device__ __forceinline__ void lora_block_store(f32x16 (&acc)[4], int mi, const
     const int r = l & 31;
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
+        // t lives in vector registers (the accumulator registers all hold the tile): the MFMAs are issued from
+        // assembly with a vector destination, the first one on a zero input
         f32x16 t;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) t[i] = 0.f;
 #pragma unroll 1
         for (int kk = 0; kk < nkk; ++kk) {
             const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni][0] + kk * 8192);
             const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni][1] + kk * 8192);
             const bf16x8 ft = __builtin_bit_cast(
                 bf16x8, *(const u32x4*)(lds_tok + row_slab_off(l & 31, 2 * kk + (l >> 5)) + mi * 4096));
-            t = LF_MFMA(join_tr(lo, hi), ft, t);
+            const bf16x8 fo = join_tr(lo, hi);
+            if (kk == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(t) : "v"(fo), "v"(ft));
+            else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(t) : "v"(fo), "v"(ft));
         }
-        asm volatile("" : "+v"(t));                  // in vector registers, where the masking below reads it
+        // the compiler does not know that these were MFMAs: the distance their result needs before the
+        // vector ALU may read it (at most 19 wait states on this chip) is put in by hand
+        asm volatile("s_nop 15\n\ts_nop 3" : "+v"(t));
         asm volatile("" : "+a"(acc[ni]));            // ... and the block stays an accumulator block up to here
         const uint32_t F = ni < 2 ? F0 : F1;
 #pragma unroll
