@@ -539,25 +539,33 @@ __device__ __forceinline__ void lora_block_store(f32x16 (&acc)[4], int mi, const
                                                  lora_bf16* out, int64_t ld, int row0_glob, int rows_left, bool col_ok,
                                                  int l) {
     const int r = l & 31;
-#pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
-        // t lives in vector registers (the accumulator registers all hold the tile): the MFMAs are issued from
-        // assembly with a vector destination, the first one on a zero input
-        f32x16 t;
+    // t = dS A^T for the four 32x32 blocks of this block row, in vector registers (the accumulator registers
+    // all hold the tile): the MFMAs are issued from assembly with a vector destination, the first of each
+    // chain on a zero input, all of them back to back before the first result is touched
+    f32x16 t[4];
 #pragma unroll 1
-        for (int kk = 0; kk < nkk; ++kk) {
+    for (int kk = 0; kk < nkk; ++kk) {
+        const bf16x8 ft = __builtin_bit_cast(
+            bf16x8, *(const u32x4*)(lds_tok + row_slab_off(l & 31, 2 * kk + (l >> 5)) + mi * 4096));
+        bf16x8 fo[4];
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) {
             const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni][0] + kk * 8192);
             const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni][1] + kk * 8192);
-            const bf16x8 ft = __builtin_bit_cast(
-                bf16x8, *(const u32x4*)(lds_tok + row_slab_off(l & 31, 2 * kk + (l >> 5)) + mi * 4096));
-            const bf16x8 fo = join_tr(lo, hi);
-            if (kk == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(t) : "v"(fo), "v"(ft));
-            else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(t) : "v"(fo), "v"(ft));
+            fo[ni] = join_tr(lo, hi);
         }
-        // the compiler does not know that these were MFMAs: the distance their result needs before the
-        // vector ALU may read it (at most 19 wait states on this chip) is put in by hand
-        asm volatile("s_nop 15\n\ts_nop 3" : "+v"(t));
-        asm volatile("" : "+a"(acc[ni]));            // ... and the block stays an accumulator block up to here
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) {
+            if (kk == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(t[ni]) : "v"(fo[ni]), "v"(ft));
+            else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(t[ni]) : "v"(fo[ni]), "v"(ft));
+        }
+    }
+    // the compiler does not know that these were MFMAs: the distance the last result needs before the
+    // vector ALU may read it (at most 19 wait states on this chip) is put in by hand
+    asm volatile("s_nop 15\n\ts_nop 3" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]));
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) {
+        asm volatile("" : "+a"(acc[ni]));            // the block stays an accumulator block up to here
         const uint32_t F = ni < 2 ? F0 : F1;
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
@@ -566,7 +574,7 @@ __device__ __forceinline__ void lora_block_store(f32x16 (&acc)[4], int mi, const
             for (int e = 0; e < 4; ++e) {
                 const int bit = (ni & 1) * 8 + g4 * 2 + (e >> 1) + (e & 1) * 16;
                 const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe((int)F, bit, 1);     // 0 or 0xFFFFFFFF
-                const float te = t[4 * g4 + e];      // (a copy: bit_cast of a vector element reads element 0)
+                const float te = t[ni][4 * g4 + e];  // (a copy: bit_cast of a vector element reads element 0)
                 v[e] = acc[ni][4 * g4 + e] + __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, te) & m);
             }
             u32x2 o;
