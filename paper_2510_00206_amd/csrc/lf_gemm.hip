@@ -185,6 +185,15 @@ struct NextSlabs {
     bool valid;
 };
 
+// Wave-uniform state of the slab pipeline.  It is advanced inside the slab step, by a few scalar
+// instructions that ride on MFMA slots, instead of being derived again from the step number at the top of
+// every step (some thirty scalar instructions between two steps, with the matrix pipe idle meanwhile).
+struct Pipe {
+    const char* src_tok; const char* src_out;     // global addresses of the NEXT slab pair's first elements
+    int64_t adv_tok, adv_out;                     // their advance per slab step, bytes
+    uint32_t rd;                                  // LDS byte offset of the stage being computed on: 0 or STAGE_BYTES
+};
+
 // Copy number J (0 .. 2*MB+PASSES-1) of the next slab pair.
 template <int MB, int J>
 __device__ __forceinline__ void issue_copy(const NextSlabs& nx) {
@@ -291,7 +300,7 @@ __device__ __forceinline__ void keep_pieces_plain(KeepShadow& k) {
 template <bool OUT_IS_COL_SLAB, int MB, int SUB, int KK_NEXT, int COPY0, int COPIES, int SLOT0, int SLOT1, int MODE, class SH>
 __device__ __forceinline__ void phase_slots(f32x16 (&acc)[MB][4], const Frags<MB>& cur, Frags<MB>& nxt,
                                             const char* lds_tok, const char* lds_out, const FragLanes& fl,
-                                            const NextSlabs& nx, SH& sh) {
+                                            const NextSlabs& nx, SH& sh, Pipe& pp) {
 #define LF_SLOT(S)                                                                                        \
     if constexpr ((S) >= SLOT0 && (S) < SLOT1 && (S) < 4 * MB) {                                         \
         acc[(S) >> 2][(S) & 3] = LF_MFMA(cur.fo[(S) & 3], cur.ft[(S) >> 2], acc[(S) >> 2][(S) & 3]);      \
@@ -317,6 +326,11 @@ __device__ __forceinline__ void phase_slots(f32x16 (&acc)[MB][4], const Frags<MB
                 issue_copy<MB, (COPY0 + ((S) >> 1))>(nx);                                                   \
         }                                                                                                 \
         shadow_slot<MB, SUB, (S)>(sh);                                                                    \
+        if constexpr (MODE == 2 && (S) == 2 * MB) {                                                       \
+            /* every copy of this step has been issued: the sources move on to the slab pair after */   \
+            pp.src_tok += pp.adv_tok;                                                                     \
+            pp.src_out += pp.adv_out;                                                                     \
+        }                                                                                                 \
         __builtin_amdgcn_sched_barrier(0);                                                                \
     }
     LF_SLOT(0) LF_SLOT(1) LF_SLOT(2) LF_SLOT(3) LF_SLOT(4) LF_SLOT(5) LF_SLOT(6) LF_SLOT(7)
@@ -329,26 +343,34 @@ __device__ __forceinline__ void phase_slots(f32x16 (&acc)[MB][4], const Frags<MB
 // (copies landed, workgroup barrier) followed by the first fragment reads of the next slab.  On entry
 // f0 holds the fragments of sub-step 0 of the current slab; on exit it holds those of the next slab.
 template <bool OUT_IS_COL_SLAB, int MB, class SH>
-__device__ __forceinline__ void slab_step(f32x16 (&acc)[MB][4], Frags<MB>& f0, Frags<MB>& f1, const char* cur_tok,
-                                          const char* cur_out, const char* nxt_tok, const char* nxt_out,
-                                          const FragLanes& fl, const NextSlabs& nx, SH& sh) {
+__device__ __forceinline__ void slab_step(f32x16 (&acc)[MB][4], Frags<MB>& f0, Frags<MB>& f1, const char* lds_tok_org,
+                                          const char* lds_out_org, uint32_t lds_copy_org, const FragLanes& fl, Pipe& pp,
+                                          const SlabLanes& lanes_tok, const SlabLanes& lanes_out, bool copy_next, SH& sh) {
     static_assert(PASSES == 8 && (MB == 4 || MB == 2), "copy schedule below assumes 8 + 2*MB copies per slab pair");
     constexpr int NS = 4 * MB;
+    // lds_tok_org / lds_out_org: the wave's origin in the token / out slab of stage 0; lds_copy_org: LDS
+    // address of stage 0 plus this wave's 1024 bytes of every copy pass
+    const uint32_t nxt = STAGE_BYTES - pp.rd;
+    const char* cur_tok = lds_tok_org + pp.rd;
+    const char* cur_out = lds_out_org + pp.rd;
+    const NextSlabs nx{pp.src_tok, pp.src_out, lanes_tok, lanes_out, lds_copy_org + nxt, lds_copy_org + nxt + TILE_BYTES,
+                       copy_next};
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (MB == 4) {
-        phase_slots<OUT_IS_COL_SLAB, MB, 0, 1, 0, 8, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh);   // copies 0..7
-        phase_slots<OUT_IS_COL_SLAB, MB, 1, 2, 8, 8, 0, NS, 0>(acc, f1, f0, cur_tok, cur_out, fl, nx, sh);   // copies 8..15
-        phase_slots<OUT_IS_COL_SLAB, MB, 2, 3, 0, 0, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh);
+        phase_slots<OUT_IS_COL_SLAB, MB, 0, 1, 0, 8, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh, pp);   // copies 0..7
+        phase_slots<OUT_IS_COL_SLAB, MB, 1, 2, 8, 8, 0, NS, 0>(acc, f1, f0, cur_tok, cur_out, fl, nx, sh, pp);   // copies 8..15
+        phase_slots<OUT_IS_COL_SLAB, MB, 2, 3, 0, 0, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh, pp);
     } else {
-        phase_slots<OUT_IS_COL_SLAB, MB, 0, 1, 0, 4, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh);   // copies 0..3
-        phase_slots<OUT_IS_COL_SLAB, MB, 1, 2, 4, 4, 0, NS, 0>(acc, f1, f0, cur_tok, cur_out, fl, nx, sh);   // copies 4..7
-        phase_slots<OUT_IS_COL_SLAB, MB, 2, 3, 8, 4, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh);   // copies 8..11
+        phase_slots<OUT_IS_COL_SLAB, MB, 0, 1, 0, 4, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh, pp);   // copies 0..3
+        phase_slots<OUT_IS_COL_SLAB, MB, 1, 2, 4, 4, 0, NS, 0>(acc, f1, f0, cur_tok, cur_out, fl, nx, sh, pp);   // copies 4..7
+        phase_slots<OUT_IS_COL_SLAB, MB, 2, 3, 8, 4, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh, pp);   // copies 8..11
     }
     // sub-step 3: first half, hand-over, second half with the next slab's first fragment reads
-    phase_slots<OUT_IS_COL_SLAB, MB, 3, 0, 0, 0, 0, NS / 2, 1>(acc, f1, f0, cur_tok, cur_out, fl, nx, sh);
+    phase_slots<OUT_IS_COL_SLAB, MB, 3, 0, 0, 0, 0, NS / 2, 1>(acc, f1, f0, cur_tok, cur_out, fl, nx, sh, pp);
     wait_slab_loads();
     __syncthreads();
-    phase_slots<OUT_IS_COL_SLAB, MB, 3, 0, 0, 0, NS / 2, NS, 2>(acc, f1, f0, nxt_tok, nxt_out, fl, nx, sh);
+    phase_slots<OUT_IS_COL_SLAB, MB, 3, 0, 0, 0, NS / 2, NS, 2>(acc, f1, f0, lds_tok_org + nxt, lds_out_org + nxt, fl, nx, sh, pp);
+    pp.rd = nxt;
 }
 
 // Accumulator element (mi, ni, i) of lane l is output row  wm*32*MB + mi*32 + (l & 31)  and output
@@ -468,24 +490,19 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     NoShadow none;
     read_frags<false>(f0, smem + tok_org, smem + out_org, fl, fl.row_off[0], 0);
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
-    for (int kt = 0; kt + 1 < nk; ++kt) {
-        const int cur = (kt & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
-        const NextSlabs nx{(const char*)(Xt + (kt + 1) * BK), (const char*)(Wt + (kt + 1) * BK), sx, sw,
-                           lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, true};
-        slab_step<false, MB>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
-                         smem + nxt + out_org, fl, nx, none);
-    }
+    Pipe pp{(const char*)(Xt + BK), (const char*)(Wt + BK), BK * 2, BK * 2, 0u};
+    for (int kt = 0; kt + 1 < nk; ++kt)
+        slab_step<false, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sx, sw, true, none);
     // the lane offsets of the LoRA slab pair are formed only now: through the main loop they would cost
     // sixteen registers that it does not have
     const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
     if (nk > 0) {
         // after the last base slab the LoRA step rides as one more slab: token operand S' [rows, r],
         // out operand B [N, r]
-        const int cur = ((nk - 1) & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
-        const NextSlabs nx{(const char*)Ssrc, (const char*)Bsrc, ss, sb,
-                           lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, has_lora && !gm.mixed};
-        slab_step<false, MB>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
-                         smem + nxt + out_org, fl, nx, none);
+        pp.src_tok = (const char*)Ssrc;
+        pp.src_out = (const char*)Bsrc;
+        slab_step<false, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sb,
+                             has_lora && !gm.mixed, none);
     }
     if (has_lora) {
         // One pass per adapter present in the tile: a single one unless the tile is mixed (FusedMultiLoRA
@@ -686,40 +703,32 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     if (nk > 0) read_frags<true>(f0, smem + tok_org, smem + out_org, fl, fl.row_off[0], 0);
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
     // slab steps 0 .. nk-2 bring the next base slab pair; the first 32 of all steps also carry the hash pieces
-    auto base_step = [&](int kt, auto& shadow) {
-        const int cur = (kt & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
-        const NextSlabs nx{(const char*)(dYt + (kt + 1) * BK), (const char*)(Wt + (int64_t)(kt + 1) * BK * p.K), sd, sw,
-                           lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, true};
-        slab_step<true, MB>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
-                            smem + nxt + out_org, fl, nx, shadow);
-    };
+    Pipe pp{(const char*)(dYt + BK), (const char*)(Wt + (int64_t)BK * p.K), BK * 2, (int64_t)BK * p.K * 2, 0u};
     int kt = 0;
     if constexpr (LORA) {
         for (; kt < min(nk - 1, FLAG_STEPS); ++kt) {
             keep_step_begin(kt);
-            base_step(kt, ks);
+            slab_step<true, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sd, sw, true, ks);
             keep_step_end(kt);
         }
     }
-    for (; kt < nk - 1; ++kt) base_step(kt, none);
+    for (; kt < nk - 1; ++kt)
+        slab_step<true, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sd, sw, true, none);
     if (nk > 0) {
         // the last base slab: the LoRA slab pair [dS | A] rides in as one more slab (nothing if there is no
         // LoRA term); its lane offsets are formed only now, the main loop has no registers for them
         const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sa = col_slab_lanes(p.K, rr, cols_valid);
-        const int cur = (kt & 1) * STAGE_BYTES, nxt = STAGE_BYTES - cur;
-        const NextSlabs nx{(const char*)dSt, (const char*)At, ss, sa,
-                           lds0 + nxt + wave_lds, lds0 + nxt + TILE_BYTES + wave_lds, LORA};
+        pp.src_tok = (const char*)dSt;
+        pp.src_out = (const char*)At;
         if constexpr (LORA) {
             // one code path for this step whatever kt is (two would have to merge all the accumulators):
             // past the 32nd step the hash pieces still run, on a step number that is never flushed
             const bool forming = kt < FLAG_STEPS;
             if (forming) keep_step_begin(kt);
-            slab_step<true, MB>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
-                                smem + nxt + out_org, fl, nx, ks);
+            slab_step<true, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sa, true, ks);
             if (forming) keep_step_end(kt);
         } else {
-            slab_step<true, MB>(acc, f0, f1, smem + cur + tok_org, smem + cur + out_org, smem + nxt + tok_org,
-                                smem + nxt + out_org, fl, nx, none);
+            slab_step<true, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sa, false, none);
         }
     }
     if constexpr (!LORA) {
