@@ -440,159 +440,70 @@ __device__ __forceinline__ int group_adapter(const GroupMap& gm, int q) {
     return __builtin_amdgcn_readfirstlane(g);
 }
 
-// ---- operation (2): Y = X W + S' B ---------------------------------------------------------------
-template <int MB>
-__global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
-    constexpr int BM = 64 * MB;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    int tm, tn;
-    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
-    RowTile rt;
-    GroupMap gm;
-    if (p.uniform_tiles) {
-        find_uniform_tile(p.tb, p.M, BM, tm, rt, gm);
-    } else {
-        if (!find_row_tile(p.tb, BM, tm, rt)) return;
-        gm.g[0] = gm.g[1] = gm.g[2] = gm.g[3] = rt.g;
-        gm.mixed = false;
-    }
-    const int n0 = tn * BN;
-    const int cols_valid = min(BN, p.N - n0);
-    const int w = threadIdx.x >> 6, wm = w & 1, wn = w >> 1;
-
-    const lora_bf16* Xt = p.X + (int64_t)rt.row_start * p.K;
-    const lora_bf16* Wt = p.W + (int64_t)n0 * p.K;
-
-    f32x16 acc[MB][4];
-
-    const int nk = p.K / BK;
-    const uint32_t lds0 = lds_addr_of(smem);
-    const FragLanes fl = frag_lanes();
-    const int tok_org = wm * (32 * MB) * 128, out_org = TILE_BYTES + wn * 128 * 128;
-    // p.r == 0 (no LoRA slab) and p.K == 0 (LoRA slab only) serve the unfused baseline's plain GEMMs.
-    const bool has_lora = p.r > 0;
-    const int rr = has_lora ? p.r : 16;
-    const SlabLanes sx = row_slab_lanes(p.K, rt.rows, 8), sw = row_slab_lanes(p.K, cols_valid, 8);
-    const lora_bf16* Ssrc = p.S + (int64_t)rt.row_start * p.r;
-    const lora_bf16* Bsrc = p.B + ((int64_t)rt.g * p.N + n0) * p.r;
-    if (nk > 0) {
-        load_slab<2 * MB>(lds0, Xt, sx);
-        load_slab(lds0 + TILE_BYTES, Wt, sw);
-    } else {
-        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
-        load_slab<2 * MB>(lds0, Ssrc, ss);
-        load_slab(lds0 + TILE_BYTES, Bsrc, sb);
-    }
-    zero_acc(acc);                                     // while the first slabs are on their way
-    wait_slab_loads();
-    __syncthreads();
-    Frags<MB> f0, f1;
-    NoShadow none;
-    read_frags<false>(f0, smem + tok_org, smem + out_org, fl, fl.row_off[0], 0);
-    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
-    Pipe pp{(const char*)(Xt + BK), (const char*)(Wt + BK), BK * 2, BK * 2, 0u};
-    for (int kt = 0; kt + 1 < nk; ++kt)
-        slab_step<false, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sx, sw, true, none);
-    // the lane offsets of the LoRA slab pair are formed only now: through the main loop they would cost
-    // sixteen registers that it does not have
-    const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
-    if (nk > 0) {
-        // after the last base slab the LoRA step rides as one more slab: token operand S' [rows, r],
-        // out operand B [N, r]
-        pp.src_tok = (const char*)Ssrc;
-        pp.src_out = (const char*)Bsrc;
-        slab_step<false, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sb,
-                             has_lora && !gm.mixed, none);
-    }
-    if (has_lora) {
-        // One pass per adapter present in the tile: a single one unless the tile is mixed (FusedMultiLoRA
-        // with tiles cut uniformly over the packed batch: one adapter per 64-row group).  The slab pair of
-        // an unmixed tile has come in with the last base slab; a mixed tile loads the S' slab of the whole
-        // tile once and the B slab once per group.  A group's sub-steps go only to the 32-row blocks inside
-        // it, so that no value of one adapter ever meets a row of another - not even multiplied by zero.
-        const int lo = (nk & 1) * STAGE_BYTES;         // the stage that holds the LoRA slab pair
-        const int l = threadIdx.x & 63;
-        const int ngroups = gm.mixed ? (rt.rows + 63) >> 6 : 1;
-#pragma unroll 1
-        for (int q = 0; q < ngroups; ++q) {
-            const int g = group_adapter(gm, q);
-            if (gm.mixed) {
-                __syncthreads();                       // every wave is done with the stage's previous contents
-                if (q == 0) load_slab<2 * MB>(lds0 + lo, Ssrc, ss);
-                load_slab(lds0 + lo + TILE_BYTES, p.B + ((int64_t)g * p.N + n0) * p.r, sb);
-                wait_slab_loads();
-                __syncthreads();
-            }
-            const int blk_lo = gm.mixed ? 64 * q : 0, blk_hi = gm.mixed ? 64 * q + 64 : BM;
-            const int nkk = p.tb.rank[g] >> 4;
-#pragma unroll 1
-            for (int kk = 0; kk < nkk; ++kk) {
-                Frags<MB> f;
-                read_frags<false>(f, smem + lo + tok_org, smem + lo + out_org, fl, row_slab_off(l & 31, 2 * kk + (l >> 5)), 0);
-#pragma unroll
-                for (int mi = 0; mi < MB; ++mi) {
-                    const int blk = wm * (32 * MB) + mi * 32;           // first tile row of the block
-                    if (blk < blk_lo || blk >= blk_hi) continue;
-#pragma unroll
-                    for (int ni = 0; ni < 4; ++ni) mfma_in_place(acc[mi][ni], f.fo[ni], f.ft[mi]);
-                }
-            }
-        }
-        mfma_in_place_done();
-    }
-    store_tile(acc, p.Y, p.N, rt.row_start, rt.rows, n0, cols_valid, wm, wn, smem);
-}
-
-// ---- operation (5): dX = dY W^T + mask*q*(dS A^T) ------------------------------------------------
-// The LoRA term of one 32-row block of a wave's sub-tile, added to the finished base-gradient
-// accumulators, rounded to bf16 and written out: t = dS A^T on a fresh accumulator per 32x32 block
-// (dS arrives scaled by s*q), t & flag, + acc, pack; the block's 32 x 128 bf16 go through 8 KB of LDS of
-// the wave's own (`stage`) so that whole 256-byte row segments are stored.  lds_tok / lds_out: the
-// LoRA slab pair (dS rows of this wave, A columns of this wave).  F0 / F1: keep flags of blocks
-// (mi, 0..1) / (mi, 2..3), bit (ni & 1) * 8 + g4 * 2 + pr for element 4*g4 + 2*pr, +16 for the next one.
-template <int MB>
-__device__ __forceinline__ void lora_block_store(f32x16 (&acc)[4], int mi, const char* lds_tok, const char* lds_out,
-                                                 const FragLanes& fl, int nkk, uint32_t F0, uint32_t F1, char* stage,
-                                                 lora_bf16* out, int64_t ld, int row0_glob, int rows_left, bool col_ok,
-                                                 int l) {
+// ---- the way out of a tile, one 32-row block of a wave's sub-tile at a time ---------------------------
+// Accumulator element (ni, i) of lane l in block row mi is tile row  wm*32*MB + mi*32 + (l & 31)  and tile
+// column  wn*128 + ni*32 + 8*(i >> 2) + 4*(l >> 5) + (i & 3): a lane owns groups of four consecutive columns
+// of one row.  Storing those 8-byte groups directly would touch 32 different rows per instruction;
+// instead the block's 32 x 128 bf16 go through 8 KB of LDS of the wave's own (`stage`: 32 rows x 32 eight-byte
+// slots, slot index XOR-ed with the row so that the 32 rows written by one instruction land in 32
+// different slots) and whole 256-byte row segments are stored, 16 bytes per lane, non-temporally: the
+// output is write-once, and keeping it out of the L2 and the memory-side cache leaves the operands (and the
+// activations that the next kernels re-read) there.
+// LORA (operation (5)): before rounding, the masked LoRA term of the block is added to the finished
+// base-gradient accumulators: t = dS A^T on a fresh accumulator per 32x32 block (dS arrives scaled by s*q),
+// t & flag, + acc.  lds_tok / lds_out: the LoRA slab pair (dS rows of this wave, A columns of this wave).
+// F0 / F1: keep flags of blocks (mi, 0..1) / (mi, 2..3), bit (ni & 1) * 8 + g4 * 2 + pr for element
+// 4*g4 + 2*pr, +16 for the next one.
+template <int MB, bool LORA>
+__device__ __forceinline__ void block_store(f32x16 (&acc)[4], int mi, const char* lds_tok, const char* lds_out,
+                                            const FragLanes& fl, int nkk, uint32_t F0, uint32_t F1, char* stage,
+                                            lora_bf16* out, int64_t ld, int row0_glob, int rows_left, bool col_ok,
+                                            int l) {
     const int r = l & 31;
-    // t = dS A^T for the four 32x32 blocks of this block row, in vector registers (the accumulator registers
-    // all hold the tile): the MFMAs are issued from assembly with a vector destination, the first of each
-    // chain on a zero input, all of them back to back before the first result is touched
     f32x16 t[4];
+    if constexpr (LORA) {
+        // t for the four 32x32 blocks of this block row, in vector registers (the accumulator registers all
+        // hold the tile): the MFMAs are issued from assembly with a vector destination, the first of each
+        // chain on a zero input, all of them back to back before the first result is touched
 #pragma unroll 1
-    for (int kk = 0; kk < nkk; ++kk) {
-        const bf16x8 ft = __builtin_bit_cast(
-            bf16x8, *(const u32x4*)(lds_tok + row_slab_off(l & 31, 2 * kk + (l >> 5)) + mi * 4096));
-        bf16x8 fo[4];
+        for (int kk = 0; kk < nkk; ++kk) {
+            const bf16x8 ft = __builtin_bit_cast(
+                bf16x8, *(const u32x4*)(lds_tok + row_slab_off(l & 31, 2 * kk + (l >> 5)) + mi * 4096));
+            bf16x8 fo[4];
 #pragma unroll
-        for (int ni = 0; ni < 4; ++ni) {
-            const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni][0] + kk * 8192);
-            const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni][1] + kk * 8192);
-            fo[ni] = join_tr(lo, hi);
-        }
+            for (int ni = 0; ni < 4; ++ni) {
+                const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni][0] + kk * 8192);
+                const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni][1] + kk * 8192);
+                fo[ni] = join_tr(lo, hi);
+            }
 #pragma unroll
-        for (int ni = 0; ni < 4; ++ni) {
-            if (kk == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(t[ni]) : "v"(fo[ni]), "v"(ft));
-            else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(t[ni]) : "v"(fo[ni]), "v"(ft));
+            for (int ni = 0; ni < 4; ++ni) {
+                if (kk == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(t[ni]) : "v"(fo[ni]), "v"(ft));
+                else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(t[ni]) : "v"(fo[ni]), "v"(ft));
+            }
         }
+        // the compiler does not know that these were MFMAs: the distance the last result needs before the
+        // vector ALU may read it (at most 19 wait states on this chip) is put in by hand
+        asm volatile("s_nop 15\n\ts_nop 3" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]));
     }
-    // the compiler does not know that these were MFMAs: the distance the last result needs before the
-    // vector ALU may read it (at most 19 wait states on this chip) is put in by hand
-    asm volatile("s_nop 15\n\ts_nop 3" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]));
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
-        asm volatile("" : "+a"(acc[ni]));            // the block stays an accumulator block up to here
+        // the block stays an accumulator block up to here (otherwise the whole tile is copied to vector
+        // registers ahead of time, which neither fit)
+        asm volatile("" : "+a"(acc[ni]));
         const uint32_t F = ni < 2 ? F0 : F1;
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
             float v[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int bit = (ni & 1) * 8 + g4 * 2 + (e >> 1) + (e & 1) * 16;
-                const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe((int)F, bit, 1);     // 0 or 0xFFFFFFFF
-                const float te = t[ni][4 * g4 + e];  // (a copy: bit_cast of a vector element reads element 0)
-                v[e] = acc[ni][4 * g4 + e] + __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, te) & m);
+                v[e] = acc[ni][4 * g4 + e];
+                if constexpr (LORA) {
+                    const int bit = (ni & 1) * 8 + g4 * 2 + (e >> 1) + (e & 1) * 16;
+                    const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe((int)F, bit, 1);     // 0 or 0xFFFFFFFF
+                    const float te = t[ni][4 * g4 + e];  // (a copy: bit_cast of a vector element reads element 0)
+                    v[e] += __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, te) & m);
+                }
             }
             u32x2 o;
             o.x = pack_bf16x2(v[0], v[1]);
@@ -608,12 +519,183 @@ __device__ __forceinline__ void lora_block_store(f32x16 (&acc)[4], int mi, const
     for (int it = 0; it < 8; ++it) {
         const int rr = it * 4 + (l >> 4);
         u32x4 v = *(const u32x4*)(stage + rr * 256 + ((j ^ (rr >> 1)) << 4));
-        if (rr & 1) v = u32x4{v.z, v.w, v.x, v.y};
+        if (rr & 1) v = u32x4{v.z, v.w, v.x, v.y};       // odd rows hold the two slots of a chunk swapped
         if (col_ok && rr < rows_left)
             __builtin_nontemporal_store(v, (u32x4*)(out + (int64_t)(row0_glob + rr) * ld + j * 8));
     }
 }
 
+// ---- tiles of a persistent workgroup ---------------------------------------------------------------
+// The kernels are launched with one workgroup per compute unit (or per tile, if there are fewer tiles);
+// a workgroup walks the tiles id, id + gridDim, ... and asks for the first slab pair of its next tile
+// before it writes out the current one, so that only its first tile waits for a slab to arrive from
+// memory and the compute unit is never without a workgroup between two tiles.
+struct TileCtx {
+    RowTile rt; GroupMap gm;
+    int c0, cols_valid;          // first output column of the tile, valid output columns
+    bool ok;
+};
+
+__device__ __forceinline__ TileCtx decode_tile(const AdapterTable& tb, int M, int bm, int uniform_tiles, int tiles_m,
+                                               int tiles_n, int id, int out_cols) {
+    TileCtx c;
+    int tm, tn;
+    tile_of_block(id, tiles_m, tiles_n, tm, tn);
+    c.ok = true;
+    if (uniform_tiles) {
+        find_uniform_tile(tb, M, bm, tm, c.rt, c.gm);
+    } else {
+        c.ok = find_row_tile(tb, bm, tm, c.rt);
+        c.gm.g[0] = c.gm.g[1] = c.gm.g[2] = c.gm.g[3] = c.rt.g;
+        c.gm.mixed = false;
+    }
+    c.c0 = tn * BN;
+    c.cols_valid = min(BN, out_cols - c.c0);
+    return c;
+}
+
+// LDS of the GEMM kernels: the two slab stages, then 32 KB in which every wave has 8 KB of its own for the
+// way out (operation (5) also parks its keep flags there, 2 KB per wave, until then).
+constexpr int WAVE_EXTRA_BYTES = 8192;
+constexpr int GEMM_LDS_TOTAL = GEMM_LDS_BYTES + NWAVES * WAVE_EXTRA_BYTES;     // 160 KB: all of a compute unit's
+
+// ---- operation (2): Y = X W + S' B ---------------------------------------------------------------
+template <int MB>
+__global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
+    constexpr int BM = 64 * MB;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int total = p.tiles_m * p.tiles_n;
+    int id = blockIdx.x;
+    TileCtx tc = decode_tile(p.tb, p.M, BM, p.uniform_tiles, p.tiles_m, p.tiles_n, id, p.N);
+    if (!tc.ok) return;
+    const int l = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wm = w & 1, wn = w >> 1;
+    const int nk = p.K / BK;
+    const uint32_t lds0 = lds_addr_of(smem);
+    const uint32_t wave_lds = w * 1024;
+    const FragLanes fl = frag_lanes();
+    const int tok_org = wm * (32 * MB) * 128, out_org = TILE_BYTES + wn * 128 * 128;
+    // p.r == 0 (no LoRA slab) and p.K == 0 (LoRA slab only) serve the unfused baseline's plain GEMMs.
+    const bool has_lora = p.r > 0;
+    const int rr = has_lora ? p.r : 16;
+    NoShadow none;
+    Pipe pp{nullptr, nullptr, BK * 2, BK * 2, 0u};
+
+    // first slab pair of the first tile
+    SlabLanes sx = row_slab_lanes(p.K, tc.rt.rows, 8), sw = row_slab_lanes(p.K, tc.cols_valid, 8);
+    if (nk > 0) {
+        load_slab<2 * MB>(lds0, p.X + (int64_t)tc.rt.row_start * p.K, sx);
+        load_slab(lds0 + TILE_BYTES, p.W + (int64_t)tc.c0 * p.K, sw);
+    }
+    for (;;) {
+        const RowTile rt = tc.rt;
+        const GroupMap gm = tc.gm;
+        const int n0 = tc.c0, cols_valid = tc.cols_valid;
+        const lora_bf16* Xt = p.X + (int64_t)rt.row_start * p.K;
+        const lora_bf16* Wt = p.W + (int64_t)n0 * p.K;
+        const lora_bf16* Ssrc = p.S + (int64_t)rt.row_start * p.r;
+        const lora_bf16* Bsrc = p.B + ((int64_t)rt.g * p.N + n0) * p.r;
+        if (nk == 0) {
+            const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
+            load_slab<2 * MB>(lds0 + pp.rd, Ssrc, ss);
+            load_slab(lds0 + pp.rd + TILE_BYTES, Bsrc, sb);
+        }
+        f32x16 acc[MB][4];
+        zero_acc(acc);                                 // while the first slabs are on their way (first tile)
+        wait_slab_loads();
+        __syncthreads();
+        Frags<MB> f0, f1;
+        read_frags<false>(f0, smem + pp.rd + tok_org, smem + pp.rd + out_org, fl, fl.row_off[0], 0);
+        pp.src_tok = (const char*)(Xt + BK);
+        pp.src_out = (const char*)(Wt + BK);
+        for (int kt = 0; kt + 1 < nk; ++kt)
+            slab_step<false, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sx, sw, true, none);
+        // the lane offsets of the LoRA slab pair are formed only now: through the main loop they would cost
+        // sixteen registers that it does not have
+        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
+        if (nk > 0) {
+            // after the last base slab the LoRA step rides as one more slab: token operand S' [rows, r],
+            // out operand B [N, r]
+            pp.src_tok = (const char*)Ssrc;
+            pp.src_out = (const char*)Bsrc;
+            slab_step<false, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sb,
+                                 has_lora && !gm.mixed, none);
+        }
+        const uint32_t lo = pp.rd;                     // the stage that holds (or receives) the LoRA slab pair
+
+        // The next tile of this workgroup: its first slab pair is asked for now, into the stage that the last
+        // base slab has just left, and arrives while the LoRA step and the way out run.  (The tile number is
+        // hidden from the optimiser, or everything derived from it would be formed - and kept in registers -
+        // before the main loop.)
+        int next = id + (int)gridDim.x;
+        asm volatile("" : "+s"(next));
+        const bool has_next = next < total;
+        if (has_next) {
+            tc = decode_tile(p.tb, p.M, BM, p.uniform_tiles, p.tiles_m, p.tiles_n, next, p.N);
+            sx = row_slab_lanes(p.K, tc.rt.rows, 8);
+            sw = row_slab_lanes(p.K, tc.cols_valid, 8);
+            if (nk > 0) {
+                load_slab<2 * MB>(lds0 + (STAGE_BYTES - lo), p.X + (int64_t)tc.rt.row_start * p.K, sx);
+                load_slab(lds0 + (STAGE_BYTES - lo) + TILE_BYTES, p.W + (int64_t)tc.c0 * p.K, sw);
+            }
+        }
+
+        if (has_lora) {
+            // One pass per adapter present in the tile: a single one unless the tile is mixed (FusedMultiLoRA
+            // with tiles cut uniformly over the packed batch: one adapter per 64-row group).  The slab pair of
+            // an unmixed tile has come in with the last base slab; a mixed tile loads the S' slab of the whole
+            // tile once and the B slab once per group.  A group's sub-steps go only to the 32-row blocks inside
+            // it, so that no value of one adapter ever meets a row of another - not even multiplied by zero.
+            const int ngroups = gm.mixed ? (rt.rows + 63) >> 6 : 1;
+#pragma unroll 1
+            for (int q = 0; q < ngroups; ++q) {
+                const int g = group_adapter(gm, q);
+                if (gm.mixed) {
+                    __syncthreads();                   // every wave is done with the stage's previous contents
+                    if (q == 0) load_slab<2 * MB>(lds0 + lo, Ssrc, ss);
+                    load_slab(lds0 + lo + TILE_BYTES, p.B + ((int64_t)g * p.N + n0) * p.r, sb);
+                    wait_slab_loads();                 // (also the next tile's first slab pair: mixed tiles are rare)
+                    __syncthreads();
+                }
+                const int blk_lo = gm.mixed ? 64 * q : 0, blk_hi = gm.mixed ? 64 * q + 64 : BM;
+                const int nkk = p.tb.rank[g] >> 4;
+#pragma unroll 1
+                for (int kk = 0; kk < nkk; ++kk) {
+                    Frags<MB> f;
+                    read_frags<false>(f, smem + lo + tok_org, smem + lo + out_org, fl, row_slab_off(l & 31, 2 * kk + (l >> 5)), 0);
+#pragma unroll
+                    for (int mi = 0; mi < MB; ++mi) {
+                        const int blk = wm * (32 * MB) + mi * 32;       // first tile row of the block
+                        if (blk < blk_lo || blk >= blk_hi) continue;
+#pragma unroll
+                        for (int ni = 0; ni < 4; ++ni) mfma_in_place(acc[mi][ni], f.fo[ni], f.ft[mi]);
+                    }
+                }
+            }
+            mfma_in_place_done();
+        }
+
+        // way out, block row by block row, through the wave's own 8 KB
+        {
+            int le = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+            asm volatile("" : "+v"(le));               // (derived values are formed here, not before the main loop)
+            char* stage = smem + GEMM_LDS_BYTES + w * WAVE_EXTRA_BYTES;
+            const bool col_ok = wn * 128 + (le & 15) * 8 < cols_valid;
+            lora_bf16* out = p.Y + (int64_t)rt.row_start * p.N + n0 + wn * 128;
+#pragma unroll
+            for (int mi = 0; mi < MB; ++mi) {
+                const int blk = wm * (32 * MB) + mi * 32;
+                block_store<MB, false>(acc[mi], mi, nullptr, nullptr, fl, 0, 0u, 0u, stage, out, p.N, blk, rt.rows - blk,
+                                       col_ok, le);
+            }
+        }
+        if (!has_next) break;
+        id = next;
+        pp.rd = STAGE_BYTES - lo;
+    }
+}
+
+// ---- operation (5): dX = dY W^T + mask*q*(dS A^T) ------------------------------------------------
 // LORA = false: the plain product dX = dY W^T (frozen linear, unfused baseline).  LORA = true: the base
 // product first, while the keep flags of the tile are formed in the shadow of its MFMAs; the LoRA slab
 // pair [dS | A] rides in as one more slab during the last base slab, and the masked LoRA term is added
@@ -771,7 +853,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
             for (int mi = 0; mi < MB; ++mi) {
                 const int blk = wm * (32 * MB) + mi * 32;          // first tile row of the block
                 if (blk < 64 * q || blk >= 64 * qe) continue;
-                lora_block_store<MB>(acc[mi], mi, lds_tok, lds_out, fl, nkk, flags_e[(2 * mi) * NTHREADS],
+                block_store<MB, true>(acc[mi], mi, lds_tok, lds_out, fl, nkk, flags_e[(2 * mi) * NTHREADS],
                                      flags_e[(2 * mi + 1) * NTHREADS], stage, out, p.K, blk, rt.rows - blk, col_ok, le);
             }
             q = qe;
@@ -819,14 +901,17 @@ static RowTiling plan_row_tiles(const AdapterTable& tb, int M, int tiles_n, int 
     return best;
 }
 
+// `persistent`: one workgroup per compute unit walks the tiles (fewer workgroups if there are fewer tiles)
 template <typename K, typename A>
-static hipError_t launch_gemm(K kernel, bool& attr_set, const A& a, hipStream_t st, int lds_bytes = GEMM_LDS_BYTES) {
+static hipError_t launch_gemm(K kernel, bool& attr_set, const A& a, hipStream_t st, int lds_bytes = GEMM_LDS_BYTES,
+                              bool persistent = false) {
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kernel, dim3(a.tiles_m * a.tiles_n), dim3(NTHREADS), lds_bytes, st, a);
+    const int tiles = a.tiles_m * a.tiles_n;
+    hipLaunchKernelGGL(kernel, dim3(persistent ? min(tiles, kComputeUnits) : tiles), dim3(NTHREADS), lds_bytes, st, a);
     return hipGetLastError();
 }
 
@@ -837,8 +922,8 @@ hipError_t launch_fwd_gemm(FwdGemmArgs a, int forced, hipStream_t st) {
     a.tiles_m = t.tiles_m;
     if (a.tiles_m == 0) return hipSuccess;
     static bool attr_set[2] = {false, false};
-    return t.bm == 256 ? launch_gemm(fwd_gemm_kernel<4>, attr_set[0], a, st)
-                       : launch_gemm(fwd_gemm_kernel<2>, attr_set[1], a, st);
+    return t.bm == 256 ? launch_gemm(fwd_gemm_kernel<4>, attr_set[0], a, st, GEMM_LDS_TOTAL, true)
+                       : launch_gemm(fwd_gemm_kernel<2>, attr_set[1], a, st, GEMM_LDS_TOTAL, true);
 }
 
 hipError_t launch_bwd_dx(DxGemmArgs a, int forced, hipStream_t st) {
