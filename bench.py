@@ -145,6 +145,9 @@ def main():
                     help="skip the measured ceilings (register-resident MFMA loop, plain HBM read) that are otherwise "
                          "taken before the warm-up steps")
     ap.add_argument("--ceilings-only", action="store_true", help="measure and print the ceilings, nothing else")
+    ap.add_argument("--gemm-compare", type=int, default=0, metavar="M",
+                    help="only time (and, under rocprofv3, expose to the counters) M x 4096 x 4096 bf16 products: the library's "
+                         "frozen-linear forward / backward GEMMs and torch.matmul (the vendor library) on the same operands")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 1 GiB device copy 10 times (reference reading for HBM byte counters)")
     args = ap.parse_args()
@@ -168,6 +171,29 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "launches": 10}))
+        return
+    if args.gemm_compare:
+        M = args.gemm_compare
+        L = workloads.custom_layer(M, 4096, 4096, 16, 2.0, 0.1, cfg=2, name="gemm_compare")
+        X, W, _, _, dY = (t.to(dev) for t in workloads.make_inputs(L))
+        Y, dX = torch.empty_like(dY), torch.empty_like(X)
+
+        def timed(fn, iters=args.steps):
+            for _ in range(max(5, iters // 4)):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(iters):
+                fn()
+            torch.cuda.synchronize()
+            return round((time.perf_counter() - t0) / iters * 1e6, 1)
+        rec = {"gemm_compare": f"{M} x 4096 x 4096 bf16", "iters": args.steps}
+        for rep in range(2):                   # twice: the first pass also settles the clocks
+            rec.update({"frozen_fwd_us": timed(lambda: binding.frozen_fwd(X, W, Y=Y)),
+                        "vendor_matmul_x_wt_us": timed(lambda: torch.matmul(X, W.t(), out=Y)),
+                        "frozen_bwd_us": timed(lambda: binding.frozen_bwd(dY, W, dX=dX)),
+                        "vendor_matmul_dy_w_us": timed(lambda: torch.matmul(dY, W, out=dX))})
+        print(json.dumps(rec))
         return
     if args.sweep:
         sweep(torch, binding, workloads, dev, args)
