@@ -41,7 +41,9 @@ def read_traffic(workload: str):
 def measure_ceilings(torch, binding, dev, operands):
     """What this GPU sustains with nothing in the way (library diagnostics, timed with events on the launch
     stream): the GEMM kernels' MFMA instruction in a register-resident loop on `operands` (values of the
-    workload's distribution), and one plain read of a 2 GiB buffer (eight times the memory-side cache)."""
+    workload's distribution), one plain read of a 2 GiB buffer (eight times the memory-side cache), and
+    plain reads the size of `operands` (what one streaming kernel of the path reads), one launch each,
+    every launch on a window of the big buffer that no earlier launch of the series has touched."""
     def timed(fn, reps, skip):
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
         evs[0].record()
@@ -61,6 +63,16 @@ def measure_ceilings(torch, binding, dev, operands):
         nbytes[0] = binding.ceiling_hbm_read(big, sink2, 4096)
     ms = timed(read, 6, 2)
     read_gbs = nbytes[0] / (ms * 1e-3) / 1e9
+    # the same read in launches of the streaming kernels' size: start-up and drain of a launch included
+    win = operands.numel() * operands.element_size() // 4096 * 4096
+    nwin = min(16, (2 << 30) // win)
+    wgs_win = 512                                # two workgroups per compute unit walk the window (the fastest shape found)
+    cursor = [0]
+
+    def read_window():
+        binding.ceiling_hbm_read(big[cursor[0] * win:(cursor[0] + 1) * win], sink2, wgs_win)
+        cursor[0] += 1
+    ms_win = timed(read_window, nwin, nwin // 4) if nwin >= 4 else None
     del big
 
     # the matrix loop last: the timed steps then start from the chip's state under its heaviest load
@@ -72,9 +84,15 @@ def measure_ceilings(torch, binding, dev, operands):
         flops[0] = binding.ceiling_mfma(operands, sink, wgs, iters)
     ms = timed(mfma, 8, 3)                      # about 60 ms in all: the sustained rate, not the first burst
     mfma_tflops = flops[0] / (ms * 1e-3) / 1e12
-    return {"mfma_bf16_tflops": round(mfma_tflops, 1), "hbm_read_gbs": round(read_gbs, 1),
-            "how": "register-resident v_mfma_f32_32x32x16_bf16 loop, 16 chains per wave, 1 wave per SIMD, operands = "
-                   "the workload's X values; plain 16-byte-per-lane read of 2 GiB"}
+    out = {"mfma_bf16_tflops": round(mfma_tflops, 1), "hbm_read_gbs": round(read_gbs, 1),
+           "how": "register-resident v_mfma_f32_32x32x16_bf16 loop, 16 chains per wave, 1 wave per SIMD, operands = "
+                  "the workload's X values; plain 16-byte-per-lane read of 2 GiB; the same read in single launches "
+                  "of sizeof(X) bytes on untouched windows"}
+    if ms_win:
+        out["hbm_read_one_launch_gbs"] = round(win / (ms_win * 1e-3) / 1e9, 1)
+        out["hbm_read_one_launch_us"] = round(ms_win * 1e3, 2)
+        out["hbm_read_one_launch_bytes"] = win
+    return out
 
 
 def sweep(torch, binding, workloads, dev, args):
@@ -357,6 +375,9 @@ def main():
         out["roofline"]["frac_of_measured"] = round(achieved / ceilings["mfma_bf16_tflops"], 4)
         out["frac_of_measured_mfma_peak"] = round(tflops / ceilings["mfma_bf16_tflops"], 4)
         out["stream_kernels_frac_of_measured_read"] = {k: round(v / ceilings["hbm_read_gbs"], 4) for k, v in stream_gbs.items()}
+        if "hbm_read_one_launch_gbs" in ceilings:
+            out["stream_kernels_frac_of_one_launch_read"] = {k: round(v / ceilings["hbm_read_one_launch_gbs"], 4)
+                                                             for k, v in stream_gbs.items()}
 
     if not args.no_cpu_baseline:
         import numpy as np
