@@ -134,3 +134,31 @@ def test_workspace_holds_every_panel_choice(lib):
     finally:
         lib.lora_set_row_tile(0)
     assert heights == {64, 128, 256, 512, 1024}
+
+
+def test_ceiling_diagnostics_validate_on_the_host(lib):
+    """The measured-ceiling launches check their arguments before anything is enqueued."""
+    ok_ptr = C.c_void_p(0x1000)
+    flops = C.c_double(0.0)
+    m = lib.lora_ceiling_mfma
+    assert m(None, ok_ptr, 256, 16, C.byref(flops), None) == 1
+    assert m(ok_ptr, None, 256, 16, C.byref(flops), None) == 1
+    assert m(ok_ptr, ok_ptr, 0, 16, C.byref(flops), None) == 4
+    assert m(ok_ptr, ok_ptr, 256, 0, C.byref(flops), None) == 4
+    assert m(C.c_void_p(0x1008), ok_ptr, 256, 16, C.byref(flops), None) == 3
+    r = lib.lora_ceiling_hbm_read
+    assert r(None, 1 << 20, ok_ptr, 256, None) == 1
+    assert r(ok_ptr, 1 << 20, None, 256, None) == 1
+    assert r(ok_ptr, 8, ok_ptr, 256, None) == 4
+    assert r(ok_ptr, 1 << 20, ok_ptr, 0, None) == 4
+    assert r(C.c_void_p(0x1004), 1 << 20, ok_ptr, 256, None) == 3
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; a request for more ends with a message before anything touches a device."""
+    import subprocess
+    import sys
+    out = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert out.returncode != 0
+    assert "ONE GPU" in (out.stderr + out.stdout)
