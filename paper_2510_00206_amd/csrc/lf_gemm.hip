@@ -561,7 +561,7 @@ constexpr int GEMM_LDS_TOTAL = GEMM_LDS_BYTES + NWAVES * WAVE_EXTRA_BYTES;     /
 
 // ---- operation (2): Y = X W + S' B ---------------------------------------------------------------
 template <int MB>
-__global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
+__global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel32(FwdGemmArgs p) {
     constexpr int BM = 64 * MB;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int total = p.tiles_m * p.tiles_n;
@@ -687,6 +687,398 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
                 const int blk = wm * (32 * MB) + mi * 32;
                 block_store<MB, false>(acc[mi], mi, nullptr, nullptr, fl, 0, 0u, 0u, stage, out, p.N, blk, rt.rows - blk,
                                        col_ok, le);
+            }
+        }
+        if (!has_next) break;
+        id = next;
+        pp.rd = STAGE_BYTES - lo;
+    }
+}
+
+// ======================================================================================================
+// The same two kernels on the 16x16x32 MFMA.  The chip is power-limited under these kernels, and a
+// register-resident loop of v_mfma_f32_16x16x32_bf16 sustains about 14 % more than one of the 32x32x16
+// instruction (half the accumulator traffic per flop): a wave's 128x128 sub-tile is 8x8 blocks of 16x16,
+// a 64-deep slab two sub-steps of 64 MFMAs.
+// ======================================================================================================
+#define LF_MFMA16X(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_bf16((a), (b), (c), 0, 0, 0)
+
+// Per-lane LDS offsets of the operand fragments (16 rows or columns x 32 contraction elements per fragment;
+// lane l holds row or column l & 15, contraction elements 8 * (l >> 4) .. +7 of the sub-step).
+//  row slab: one 16-byte read at row_off[sub-step] + 2048 bytes per 16-row block;
+//  col slab (operation (5)): two transposing reads, contraction rows 32*sub + 8*(l >> 4) + {0..3 | 4..7}, at
+//            (col_off ^ (block << 5)) + 16384 * sub {+ 2048}.
+struct FragLanes16 { int row_off[2]; int col_off; };
+
+template <bool COL_SLAB>
+__device__ __forceinline__ FragLanes16 frag_lanes16(int wn) {
+    const int l = threadIdx.x & 63;
+    FragLanes16 f;
+    f.row_off[0] = row_slab_off(l & 15, l >> 4);
+    f.row_off[1] = row_slab_off(l & 15, 4 + (l >> 4));
+    f.col_off = COL_SLAB ? col_slab16_tr_off(8 * (l >> 4), wn * 128, l & 15) : 0;
+    return f;
+}
+
+// Fragments of a wave: the out operand double-buffered by sub-step, the token operand in place (block mi is
+// reloaded for the next sub-step as soon as the eight MFMAs of its row have been issued).
+template <int MB> struct Frags16 { bf16x8 fo[2][8]; bf16x8 ft[2 * MB]; };
+
+template <bool COL_SLAB>
+__device__ __forceinline__ bf16x8 read_out_frag16(const char* lds_out, const FragLanes16& fl, int blk, int sub) {
+    if constexpr (COL_SLAB) {
+        const int off = (fl.col_off ^ (blk << 5)) + sub * 16384;
+        const s16x4 lo = lds_read_tr(lds_out, off);
+        const s16x4 hi = lds_read_tr(lds_out, off + 2048);
+        return join_tr(lo, hi);
+    } else {
+        return __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_out + fl.row_off[sub] + blk * 2048));
+    }
+}
+__device__ __forceinline__ bf16x8 read_tok_frag16(const char* lds_tok, const FragLanes16& fl, int blk, int sub) {
+    return __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_tok + fl.row_off[sub] + blk * 2048));
+}
+
+// all fragments of sub-step 0 of a slab (start of a tile)
+template <bool COL_SLAB, int MB>
+__device__ __forceinline__ void read_frags16(Frags16<MB>& f, const char* lds_tok, const char* lds_out, const FragLanes16& fl) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) f.fo[0][k] = read_out_frag16<COL_SLAB>(lds_out, fl, k, 0);
+#pragma unroll
+    for (int mi = 0; mi < 2 * MB; ++mi) f.ft[mi] = read_tok_frag16(lds_tok, fl, mi, 0);
+}
+
+// What rides on MFMA slot s of sub-step `sub` (s = 8 * token block + out block; -1: nothing).
+template <int MB> struct Sched16 {
+    static constexpr int TB = 2 * MB, SS = 8 * TB;
+    static constexpr int HO = MB == 4 ? 36 : 14;          // sub-step 1: hand-over after this slot
+    // read of out fragment k for the next sub-step (sub-step 0: of this slab; sub-step 1: of the next slab)
+    static constexpr int fo_read(int sub, int s) {
+        if (sub == 0) return MB == 4 ? ((s & 7) == 4 ? s >> 3 : -1) : ((s & 3) == 0 ? s >> 2 : -1);
+        const int d = s - (HO + 1);
+        return d >= 0 && d < 16 && (d & 1) == 0 ? d >> 1 : -1;
+    }
+    // reload of token fragment mi; slot 1 brings the last block's fragment of THIS sub-step (its row is not
+    // over when the others are reloaded), the others that of the next sub-step
+    static constexpr int ft_read(int sub, int s) {
+        if (s == 1) return TB - 1;
+        if (sub == 0) {
+            if (MB == 4) return (s & 7) == 1 && s >= 9 ? (s >> 3) - 1 : -1;       // 9, 17, .. 57 -> 0 .. 6
+            return (s & 7) == 2 && s >= 10 ? (s >> 3) - 1 : -1;                   // 10, 18, 26 -> 0 .. 2
+        }
+        if (MB == 4) return s >= 38 && s <= 46 && !(s & 1) ? (s - 38) >> 1 : s == 48 ? 5 : s == 56 ? 6 : -1;
+        return s == 16 ? 0 : s == 18 ? 1 : s == 24 ? 2 : -1;
+    }
+    // copy number (0 .. 2*MB + 7) of the next slab pair
+    static constexpr int copy_at(int sub, int s) {
+        if (sub != 0) return -1;
+        if (MB == 4) return (s & 3) == 2 ? s >> 2 : -1;                           // 2, 6, .. 62 -> 0 .. 15
+        return (s & 1) && s >= 3 && s <= 25 ? (s - 3) >> 1 : -1;                  // 3, 5, .. 25 -> 0 .. 11
+    }
+};
+
+// (operation (5) hangs its hash pieces on free slots; nothing for the others)
+template <int MB, int SUB, int S> __device__ __forceinline__ void shadow_slot16(NoShadow&) {}
+
+// LDS side of one slab step: where the current slab pair lies and where the next one goes.
+struct StepLds {
+    const char* cur_tok; const char* cur_out;     // this wave's origin in the slabs being computed on
+    const char* nxt_tok; const char* nxt_out;     // ... and in the slabs being filled
+};
+
+template <bool COL_SLAB, int MB, int S, class SH>
+__device__ __forceinline__ void slots16(f32x4 (&acc)[2 * MB][8], Frags16<MB>& f, const StepLds& L, const FragLanes16& fl,
+                                        const NextSlabs& nx, bool read_next, SH& sh, Pipe& pp) {
+    using SC = Sched16<MB>;
+    constexpr int sub = S / SC::SS, s = S % SC::SS, mi = s >> 3, ni = s & 7;
+    acc[mi][ni] = LF_MFMA16X(f.fo[sub][ni], f.ft[mi], acc[mi][ni]);
+    constexpr int k = SC::fo_read(sub, s);
+    if constexpr (k >= 0) {
+        if constexpr (sub == 0) f.fo[1][k] = read_out_frag16<COL_SLAB>(L.cur_out, fl, k, 1);
+        else if (read_next) f.fo[0][k] = read_out_frag16<COL_SLAB>(L.nxt_out, fl, k, 0);
+    }
+    constexpr int m = SC::ft_read(sub, s);
+    if constexpr (m >= 0) {
+        if constexpr (s == 1) f.ft[m] = read_tok_frag16(L.cur_tok, fl, m, sub);
+        else if constexpr (sub == 0) f.ft[m] = read_tok_frag16(L.cur_tok, fl, m, 1);
+        else if (read_next) f.ft[m] = read_tok_frag16(L.nxt_tok, fl, m, 0);
+    }
+    constexpr int j = SC::copy_at(sub, s);
+    if constexpr (j >= 0) issue_copy<MB, j>(nx);
+    shadow_slot16<MB, sub, s>(sh);
+    if constexpr (sub == 1 && s == 0) {
+        // every copy of this step has been issued: the sources move on to the slab pair after
+        pp.src_tok += pp.adv_tok;
+        pp.src_out += pp.adv_out;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (sub == 1 && s == SC::HO) {
+        wait_slab_loads();
+        __syncthreads();
+    }
+    if constexpr (S + 1 < 2 * SC::SS) slots16<COL_SLAB, MB, S + 1>(acc, f, L, fl, nx, read_next, sh, pp);
+}
+
+// One 64-deep slab pair: two sub-steps of 16*MB MFMAs; the copies of the next slab pair ride on sub-step 0,
+// the hand-over (copies landed, workgroup barrier) sits in sub-step 1 and is followed by the first fragment
+// reads of the next slab (if read_next).  On entry f holds the fragments of sub-step 0 of the current slab.
+template <bool COL_SLAB, int MB, class SH>
+__device__ __forceinline__ void slab_step16(f32x4 (&acc)[2 * MB][8], Frags16<MB>& f, const char* lds_tok_org,
+                                            const char* lds_out_org, uint32_t lds_copy_org, const FragLanes16& fl, Pipe& pp,
+                                            const SlabLanes& lanes_tok, const SlabLanes& lanes_out, bool copy_next,
+                                            bool read_next, SH& sh) {
+    const uint32_t nxt = STAGE_BYTES - pp.rd;
+    const StepLds L{lds_tok_org + pp.rd, lds_out_org + pp.rd, lds_tok_org + nxt, lds_out_org + nxt};
+    const NextSlabs nx{pp.src_tok, pp.src_out, lanes_tok, lanes_out, lds_copy_org + nxt, lds_copy_org + nxt + TILE_BYTES,
+                       copy_next};
+    __builtin_amdgcn_sched_barrier(0);
+    slots16<COL_SLAB, MB, 0>(acc, f, L, fl, nx, read_next, sh, pp);
+    pp.rd = nxt;
+}
+
+template <int MB>
+__device__ __forceinline__ void zero_acc16(f32x4 (&acc)[2 * MB][8]) {
+#pragma unroll
+    for (int mi = 0; mi < 2 * MB; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 8; ++ni) acc[mi][ni] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // pin the register writes here (between the issue of the first slab copies and the wait for them)
+#pragma unroll
+    for (int mi = 0; mi < 2 * MB; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 8; ++ni) asm volatile("" : "+a"(acc[mi][ni]));
+}
+
+// An MFMA under wave-uniform control flow with the accumulator tied to itself (see mfma_in_place).
+__device__ __forceinline__ void mfma16_in_place(f32x4& c, bf16x8 a, bf16x8 b) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+
+// Lanes whose contraction elements lie at or past `valid_chunks` 16-byte chunks (8 elements each) of a rank-wide
+// slab get a zero fragment: the slab's LDS rows hold duplicates there (the copies clamp), and a 32-deep MFMA
+// sub-step reaches past a rank of 16 (or 48).
+__device__ __forceinline__ bf16x8 zero_past_rank(bf16x8 v, int chunk, int valid_chunks) {
+    u32x4 u = __builtin_bit_cast(u32x4, v);
+    if (chunk >= valid_chunks) u = u32x4{0u, 0u, 0u, 0u};
+    return __builtin_bit_cast(bf16x8, u);
+}
+
+// ---- the way out of a tile, two 16-row blocks of a wave's sub-tile at a time ---------------------------
+// Accumulator element e of block (mi, ni) in lane l is tile row  wm*32*MB + mi*16 + (l & 15)  and tile column
+// wn*128 + ni*16 + 4*(l >> 4) + e: a lane owns four consecutive columns of one row per block.  The 32 x 128 bf16
+// of a block-row pair go through 8 KB of LDS of the wave's own (`stage`: 32 rows x 32 eight-byte slots, slot
+// index XOR-ed with 2 * (row & 15) so that the 32 lanes served in one cycle - 16 rows x 2 slots - land in 32
+// different slots) and whole 256-byte row segments are stored, 16 bytes per lane, non-temporally.
+// LORA (operation (5)): before rounding, the masked LoRA term is added to the finished base-gradient
+// accumulators: t = dS A^T per 16x16 block by MFMAs with a vector-register destination (dS arrives scaled by
+// s*q), t & flag, + acc.  F[h]: keep flags of block row 2*bp + h, bit ni*2 + pr for element 2*pr, +16 for 2*pr+1.
+template <int MB, bool LORA>
+__device__ __forceinline__ void block_store16(f32x4 (&acc)[2 * MB][8], int bp, const char* lds_tok, const char* lds_out,
+                                              const FragLanes16& fl, int rank_chunks, uint32_t F0, uint32_t F1, char* stage,
+                                              lora_bf16* out, int64_t ld, int row0_glob, int rows_left, bool col_ok,
+                                              int l) {
+    f32x4 t[2][8];
+    if constexpr (LORA) {
+        const int nkk = (rank_chunks + 3) >> 2;
+#pragma unroll 1
+        for (int kk = 0; kk < nkk; ++kk) {
+            const int chunk = 4 * kk + (l >> 4);
+            bf16x8 ft[2], fo[8];
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                ft[h] = zero_past_rank(__builtin_bit_cast(bf16x8, *(const u32x4*)(lds_tok + row_slab_off(l & 15, chunk) +
+                                                                                    (2 * bp + h) * 2048)), chunk, rank_chunks);
+#pragma unroll
+            for (int ni = 0; ni < 8; ++ni) {
+                // contraction rows 32*kk + 8*(l >> 4) + {0..3 | 4..7} of the A slab
+                const int off = (fl.col_off ^ (ni << 5)) + kk * 16384;
+                fo[ni] = zero_past_rank(join_tr(lds_read_tr(lds_out, off), lds_read_tr(lds_out, off + 2048)), chunk, rank_chunks);
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int ni = 0; ni < 8; ++ni) {
+                    if (kk == 0) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=&v"(t[h][ni]) : "v"(fo[ni]), "v"(ft[h]));
+                    else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(t[h][ni]) : "v"(fo[ni]), "v"(ft[h]));
+                }
+        }
+        // the compiler does not know that these were MFMAs: the distance the last result needs before the
+        // vector ALU may read it is put in by hand
+        asm volatile("s_nop 15\n\ts_nop 3" : "+v"(t[1][4]), "+v"(t[1][5]), "+v"(t[1][6]), "+v"(t[1][7]));
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int r = h * 16 + (l & 15);
+        const uint32_t F = h ? F1 : F0;
+#pragma unroll
+        for (int ni = 0; ni < 8; ++ni) {
+            asm volatile("" : "+a"(acc[2 * bp + h][ni]));      // stays an accumulator block up to here
+            float v[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[e] = acc[2 * bp + h][ni][e];
+                if constexpr (LORA) {
+                    const int bit = ni * 2 + (e >> 1) + (e & 1) * 16;
+                    const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe((int)F, bit, 1);     // 0 or 0xFFFFFFFF
+                    const float te = t[h][ni][e];        // (a copy: bit_cast of a vector element reads element 0)
+                    v[e] += __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, te) & m);
+                }
+            }
+            u32x2 o;
+            o.x = pack_bf16x2(v[0], v[1]);
+            o.y = pack_bf16x2(v[2], v[3]);
+            const int slot = ni * 4 + (l >> 4);
+            *(u32x2*)(stage + r * 256 + ((slot ^ ((r & 15) << 1)) << 3)) = o;
+        }
+    }
+    // LDS operations of one wave complete in order: the reads below see the writes above, and the next
+    // pair's writes come after these reads
+    const int j = l & 15;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+        const int rr = it * 4 + (l >> 4);
+        const u32x4 v = *(const u32x4*)(stage + rr * 256 + ((j ^ (rr & 15)) << 4));
+        if (col_ok && rr < rows_left)
+            __builtin_nontemporal_store(v, (u32x4*)(out + (int64_t)(row0_glob + rr) * ld + j * 8));
+    }
+}
+
+
+// ---- operation (2): Y = X W + S' B ---------------------------------------------------------------
+template <int MB>
+__global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
+    constexpr int BM = 64 * MB, TB = 2 * MB;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int total = p.tiles_m * p.tiles_n;
+    int id = blockIdx.x;
+    TileCtx tc = decode_tile(p.tb, p.M, BM, p.uniform_tiles, p.tiles_m, p.tiles_n, id, p.N);
+    if (!tc.ok) return;
+    const int l = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wm = w & 1, wn = w >> 1;
+    const int nk = p.K / BK;
+    const uint32_t lds0 = lds_addr_of(smem);
+    const uint32_t wave_lds = w * 1024;
+    const FragLanes16 fl = frag_lanes16<false>(wn);
+    const int tok_org = wm * (32 * MB) * 128, out_org = TILE_BYTES + wn * 128 * 128;
+    // p.r == 0 (no LoRA slab) and p.K == 0 (LoRA slab only) serve the unfused baseline's plain GEMMs.
+    const bool has_lora = p.r > 0;
+    const int rr = has_lora ? p.r : 16;
+    NoShadow none;
+    Pipe pp{nullptr, nullptr, BK * 2, BK * 2, 0u};
+
+    // first slab pair of the first tile
+    SlabLanes sx = row_slab_lanes(p.K, tc.rt.rows, 8), sw = row_slab_lanes(p.K, tc.cols_valid, 8);
+    if (nk > 0) {
+        load_slab<2 * MB>(lds0, p.X + (int64_t)tc.rt.row_start * p.K, sx);
+        load_slab(lds0 + TILE_BYTES, p.W + (int64_t)tc.c0 * p.K, sw);
+    }
+    for (;;) {
+        const RowTile rt = tc.rt;
+        const GroupMap gm = tc.gm;
+        const int n0 = tc.c0, cols_valid = tc.cols_valid;
+        const lora_bf16* Xt = p.X + (int64_t)rt.row_start * p.K;
+        const lora_bf16* Wt = p.W + (int64_t)n0 * p.K;
+        const lora_bf16* Ssrc = p.S + (int64_t)rt.row_start * p.r;
+        const lora_bf16* Bsrc = p.B + ((int64_t)rt.g * p.N + n0) * p.r;
+        if (nk == 0) {
+            const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
+            load_slab<2 * MB>(lds0 + pp.rd, Ssrc, ss);
+            load_slab(lds0 + pp.rd + TILE_BYTES, Bsrc, sb);
+        }
+        f32x4 acc[TB][8];
+        zero_acc16<MB>(acc);                           // while the first slabs are on their way (first tile)
+        wait_slab_loads();
+        __syncthreads();
+        Frags16<MB> f;
+        if (nk > 0) read_frags16<false, MB>(f, smem + pp.rd + tok_org, smem + pp.rd + out_org, fl);
+        pp.src_tok = (const char*)(Xt + BK);
+        pp.src_out = (const char*)(Wt + BK);
+        for (int kt = 0; kt + 1 < nk; ++kt)
+            slab_step16<false, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sx, sw, true, true, none);
+        // the lane offsets of the LoRA slab pair are formed only now: through the main loop they would cost
+        // sixteen registers that it does not have
+        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
+        if (nk > 0) {
+            // after the last base slab the LoRA step rides as one more slab: token operand S' [rows, r],
+            // out operand B [N, r]
+            pp.src_tok = (const char*)Ssrc;
+            pp.src_out = (const char*)Bsrc;
+            slab_step16<false, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sb,
+                                   has_lora && !gm.mixed, false, none);
+        }
+        const uint32_t lo = pp.rd;                     // the stage that holds (or receives) the LoRA slab pair
+
+        // The next tile of this workgroup: its first slab pair is asked for now, into the stage that the last
+        // base slab has just left, and arrives while the LoRA step and the way out run.  (The tile number is
+        // hidden from the optimiser, or everything derived from it would be formed - and kept in registers -
+        // before the main loop.)
+        int next = id + (int)gridDim.x;
+        asm volatile("" : "+s"(next));
+        const bool has_next = next < total;
+        if (has_next) {
+            tc = decode_tile(p.tb, p.M, BM, p.uniform_tiles, p.tiles_m, p.tiles_n, next, p.N);
+            sx = row_slab_lanes(p.K, tc.rt.rows, 8);
+            sw = row_slab_lanes(p.K, tc.cols_valid, 8);
+            if (nk > 0) {
+                load_slab<2 * MB>(lds0 + (STAGE_BYTES - lo), p.X + (int64_t)tc.rt.row_start * p.K, sx);
+                load_slab(lds0 + (STAGE_BYTES - lo) + TILE_BYTES, p.W + (int64_t)tc.c0 * p.K, sw);
+            }
+        }
+
+        if (has_lora) {
+            // One pass per adapter present in the tile: a single one unless the tile is mixed (FusedMultiLoRA
+            // with tiles cut uniformly over the packed batch: one adapter per 64-row group).  The slab pair of
+            // an unmixed tile has come in with the last base slab; a mixed tile loads the S' slab of the whole
+            // tile once and the B slab once per group.  A group's sub-steps go only to the 16-row blocks inside
+            // it, so that no value of one adapter ever meets a row of another - not even multiplied by zero.
+            const int ngroups = gm.mixed ? (rt.rows + 63) >> 6 : 1;
+#pragma unroll 1
+            for (int q = 0; q < ngroups; ++q) {
+                const int g = group_adapter(gm, q);
+                if (gm.mixed) {
+                    __syncthreads();                   // every wave is done with the stage's previous contents
+                    if (q == 0) load_slab<2 * MB>(lds0 + lo, Ssrc, ss);
+                    load_slab(lds0 + lo + TILE_BYTES, p.B + ((int64_t)g * p.N + n0) * p.r, sb);
+                    wait_slab_loads();                 // (also the next tile's first slab pair: mixed tiles are rare)
+                    __syncthreads();
+                }
+                const int blk_lo = gm.mixed ? 64 * q : 0, blk_hi = gm.mixed ? 64 * q + 64 : BM;
+                const int rank_chunks = p.tb.rank[g] >> 3, nkk = (rank_chunks + 3) >> 2;
+#pragma unroll 1
+                for (int kk = 0; kk < nkk; ++kk) {
+                    const int chunk = 4 * kk + (l >> 4);
+                    const int off = row_slab_off(l & 15, chunk);
+                    bf16x8 fo[8];
+#pragma unroll
+                    for (int ni = 0; ni < 8; ++ni)
+                        fo[ni] = zero_past_rank(__builtin_bit_cast(bf16x8, *(const u32x4*)(smem + lo + out_org + off + ni * 2048)),
+                                                chunk, rank_chunks);
+#pragma unroll
+                    for (int mi = 0; mi < TB; ++mi) {
+                        const int blk = wm * (32 * MB) + mi * 16;       // first tile row of the block
+                        if (blk < blk_lo || blk >= blk_hi) continue;
+                        const bf16x8 ft = zero_past_rank(
+                            __builtin_bit_cast(bf16x8, *(const u32x4*)(smem + lo + tok_org + off + mi * 2048)), chunk, rank_chunks);
+#pragma unroll
+                        for (int ni = 0; ni < 8; ++ni) mfma16_in_place(acc[mi][ni], fo[ni], ft);
+                    }
+                }
+            }
+            mfma_in_place_done();
+        }
+
+        // way out, pair of block rows by pair, through the wave's own 8 KB
+        {
+            int le = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+            asm volatile("" : "+v"(le));               // (derived values are formed here, not before the main loop)
+            char* stage = smem + GEMM_LDS_BYTES + w * WAVE_EXTRA_BYTES;
+            const bool col_ok = wn * 128 + (le & 15) * 8 < cols_valid;
+            lora_bf16* out = p.Y + (int64_t)rt.row_start * p.N + n0 + wn * 128;
+#pragma unroll
+            for (int bp = 0; bp < MB; ++bp) {
+                const int blk = wm * (32 * MB) + bp * 32;
+                block_store16<MB, false>(acc, bp, nullptr, nullptr, fl, 0, 0u, 0u, stage, out, p.N, blk, rt.rows - blk,
+                                         col_ok, le);
             }
         }
         if (!has_next) break;
