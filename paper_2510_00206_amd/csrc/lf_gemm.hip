@@ -849,9 +849,12 @@ __device__ __forceinline__ void zero_acc16(f32x4 (&acc)[2 * MB][8]) {
         for (int ni = 0; ni < 8; ++ni) asm volatile("" : "+a"(acc[mi][ni]));
 }
 
-// An MFMA under wave-uniform control flow with the accumulator tied to itself (see mfma_in_place).
+// An MFMA under wave-uniform control flow with the accumulator tied to itself (see mfma_in_place).  Its
+// operands may have been written by the vector ALU just before (zero_past_rank): the compiler keeps the
+// distance an MFMA needs from such a write for its own MFMAs, not for one inside an assembly statement, so
+// the two wait states are part of the statement.
 __device__ __forceinline__ void mfma16_in_place(f32x4& c, bf16x8 a, bf16x8 b) {
-    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+    asm volatile("s_nop 1\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 
 // Lanes whose contraction elements lie at or past `valid_chunks` 16-byte chunks (8 elements each) of a rank-wide
@@ -898,13 +901,17 @@ __device__ __forceinline__ void block_store16(f32x4 (&acc)[2 * MB][8], int bp, c
             for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int ni = 0; ni < 8; ++ni) {
-                    if (kk == 0) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=&v"(t[h][ni]) : "v"(fo[ni]), "v"(ft[h]));
-                    else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(t[h][ni]) : "v"(fo[ni]), "v"(ft[h]));
+                    // (s_nop 1: the operands may come straight from the vector ALU, see mfma16_in_place)
+                    if (kk == 0) asm volatile("s_nop 1\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=&v"(t[h][ni]) : "v"(fo[ni]), "v"(ft[h]));
+                    else asm volatile("s_nop 1\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(t[h][ni]) : "v"(fo[ni]), "v"(ft[h]));
                 }
         }
         // the compiler does not know that these were MFMAs: the distance the last result needs before the
         // vector ALU may read it is put in by hand
-        asm volatile("s_nop 15\n\ts_nop 3" : "+v"(t[1][4]), "+v"(t[1][5]), "+v"(t[1][6]), "+v"(t[1][7]));
+        asm volatile("s_nop 15\n\ts_nop 3"
+                     : "+v"(t[0][0]), "+v"(t[0][1]), "+v"(t[0][2]), "+v"(t[0][3]), "+v"(t[0][4]), "+v"(t[0][5]), "+v"(t[0][6]),
+                       "+v"(t[0][7]), "+v"(t[1][0]), "+v"(t[1][1]), "+v"(t[1][2]), "+v"(t[1][3]), "+v"(t[1][4]), "+v"(t[1][5]),
+                       "+v"(t[1][6]), "+v"(t[1][7]));
     }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -1093,7 +1100,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
 // pair [dS | A] rides in as one more slab during the last base slab, and the masked LoRA term is added
 // block by block on the way out.  p.N == 0 (LoRA term only) serves the unfused baseline.
 template <int MB, bool LORA>
-__global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
+__global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel32(DxGemmArgs p) {
     constexpr int BM = 64 * MB;
     constexpr int WPS = MB == 4 ? 4 : 2;             // hash words per slab step and lane
     constexpr int FLAG_STEPS = 32 * MB / WPS;        // slab steps until the tile's flags are complete: 32
@@ -1247,6 +1254,256 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
                 if (blk < 64 * q || blk >= 64 * qe) continue;
                 block_store<MB, true>(acc[mi], mi, lds_tok, lds_out, fl, nkk, flags_e[(2 * mi) * NTHREADS],
                                      flags_e[(2 * mi + 1) * NTHREADS], stage, out, p.K, blk, rt.rows - blk, col_ok, le);
+            }
+            q = qe;
+        }
+    }
+}
+
+// ---- dropout keep flags formed in the shadow of the matrix work (operation (5)), 16x16 blocks --------
+// Lane l of a wave owns, in 16x16 block (mi, ni), columns ni*16 + 4*(l >> 4) + {0..3} of tile row mi*16 + (l & 15):
+// column pairs cp0 + ni*8 + {0, 1} with cp0 the lane's first pair.  Word number of a block row wd = ni*2 + pr; one
+// flag register per block row, bit wd for the even column and bit wd + 16 for the odd one.  A slab step forms WPS
+// words (4 in a 256-row tile, 2 in a 128-row tile), so the flags of a tile are complete after 32 slab steps.
+// The MFMA here takes 16 cycles, so a piece is at most three full-rate instructions or one 32-bit multiply
+// (16 cycles by itself); the words of a step go through the six stages two at a time, alternating, so that a
+// piece never waits for the multiply before it.
+struct KeepShadow16 {
+    uint32_t xb, x[2], t[2], m4, fcur;     // vector registers: running hash state, flags of the current register
+    uint32_t x0, rkb;                      // row keys of the current block row: rk.a + cp0 * kGold, rk.b
+    uint32_t xoff, shift, tm1;             // wave-uniform: pair offset * kGold and flag position of this step; packed T-1
+};
+
+// Piece PID of a slab step: round PID / 12 handles words J = 2*round + {0, 1}; stage (PID % 12) >> 1 of
+//   x = x0 + pair*kGold; x ^= x>>16 | x *= M1 | x += rk.b; x ^= x>>15 | x *= M2 | x ^= x>>16; saturating x - (T-1) | flags
+template <int WPS, int PID>
+__device__ __forceinline__ void keep_piece16(KeepShadow16& k) {
+    constexpr int RND = PID / 12, Q = PID % 12, ST = Q >> 1, R = Q & 1, J = 2 * RND + R;
+    constexpr uint32_t CJ = (uint32_t)((J >> 1) * 8 + (J & 1)) * kGold;      // pairs 0, 1, 8, 9 past the step's first
+    if constexpr (ST == 0 && J == 0) {
+        asm volatile("v_add_u32 %0, %4, %3\n\tv_lshrrev_b32 %1, 16, %0\n\tv_xor_b32 %2, %0, %1"
+                     : "=&v"(k.xb), "=&v"(k.t[R]), "=&v"(k.x[R]) : "v"(k.x0), "s"(k.xoff));
+    } else if constexpr (ST == 0) {
+        asm volatile("v_add_u32 %0, %3, %2\n\tv_lshrrev_b32 %1, 16, %0\n\tv_xor_b32 %0, %0, %1"
+                     : "=&v"(k.x[R]), "=&v"(k.t[R]) : "v"(k.xb), "s"(CJ));
+    } else if constexpr (ST == 1) {
+        asm volatile("v_mul_lo_u32 %0, %0, %1" : "+v"(k.x[R]) : "s"(kM1));
+    } else if constexpr (ST == 2) {
+        asm volatile("v_add_u32 %0, %0, %2\n\tv_lshrrev_b32 %1, 15, %0\n\tv_xor_b32 %0, %0, %1"
+                     : "+v"(k.x[R]), "=&v"(k.t[R]) : "v"(k.rkb));
+    } else if constexpr (ST == 3) {
+        asm volatile("v_mul_lo_u32 %0, %0, %1" : "+v"(k.x[R]) : "s"(kM2));
+    } else if constexpr (ST == 4) {
+        // saturating 16-bit halves minus (T-1): zero exactly where the half is below T
+        asm volatile("v_lshrrev_b32 %1, 16, %0\n\tv_xor_b32 %0, %0, %1\n\tv_pk_sub_u16 %1, %0, %2 clamp"
+                     : "+v"(k.x[R]), "=&v"(k.t[R]) : "s"(k.tm1));
+    } else {
+        // keep flag of a 16-bit half: min(that, 1), both halves at once, shifted to the word's position
+        if constexpr (J == 0)
+            asm volatile("v_pk_min_u16 %0, %1, %2" : "=v"(k.m4) : "v"(k.t[R]), "s"(0x00010001u));
+        else
+            asm volatile("v_pk_min_u16 %1, %1, %2\n\tv_lshl_or_b32 %0, %1, %3, %0"
+                         : "+v"(k.m4), "+v"(k.t[R]) : "s"(0x00010001u), "n"(J));
+        if constexpr (J == WPS - 1)
+            asm volatile("v_lshl_or_b32 %0, %1, %2, %0" : "+v"(k.fcur) : "v"(k.m4), "s"(k.shift));
+    }
+}
+
+// pieces ride on slots 2 .. 6*WPS+1 of sub-step 1 (before the hand-over; slot 1 carries a fragment read)
+template <int MB, int SUB, int S> __device__ __forceinline__ void shadow_slot16(KeepShadow16& k) {
+    constexpr int WPS = MB == 4 ? 4 : 2;
+    if constexpr (SUB == 1 && S >= 2 && S < 2 + 6 * WPS) keep_piece16<WPS, S - 2>(k);
+}
+// the same pieces outside any slab step (tiles with fewer than 32 slab steps)
+template <int WPS, int PID = 0>
+__device__ __forceinline__ void keep_pieces_plain16(KeepShadow16& k) {
+    if constexpr (PID < 6 * WPS) {
+        keep_piece16<WPS, PID>(k);
+        keep_pieces_plain16<WPS, PID + 1>(k);
+    }
+}
+
+// Column-operand slab lanes for the 16x16x32 layout (see col_slab16_swz): 64 contraction rows x 256 output
+// columns, each row 32 chunks (512 B).  Wave w, pass i fills rows 2*(NWAVES*i + w), +1.
+__device__ __forceinline__ SlabLanes col_slab16_lanes(int64_t ld, int rows_valid, int cols_valid) {
+    const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
+    SlabLanes s;
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i) {
+        const int row = 2 * (NWAVES * i + w) + (l >> 5);
+        const int chunk = min((l & 31) ^ col_slab16_swz(row), (cols_valid >> 3) - 1);
+        s.off[i] = (uint32_t)((min(row, rows_valid - 1) * ld + chunk * 8) * 2);
+    }
+    return s;
+}
+
+// ---- operation (5): dX = dY W^T + mask*q*(dS A^T) ------------------------------------------------
+// LORA = false: the plain product dX = dY W^T (frozen linear, unfused baseline).  LORA = true: the base
+// product first, while the keep flags of the tile are formed in the shadow of its MFMAs; the LoRA slab
+// pair [dS | A] rides in as one more slab during the last base slab, and the masked LoRA term is added
+// pair of block rows by pair on the way out.  p.N == 0 (LoRA term only) serves the unfused baseline.
+template <int MB, bool LORA>
+__global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
+    constexpr int BM = 64 * MB, TB = 2 * MB;
+    constexpr int WPS = MB == 4 ? 4 : 2;             // hash words per slab step and lane
+    constexpr int FLAG_STEPS = 16 * TB / WPS;        // slab steps until the tile's flags are complete: 32
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    int tm, tn;
+    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+    RowTile rt;
+    GroupMap gm;
+    if (p.uniform_tiles) {
+        find_uniform_tile(p.tb, p.M, BM, tm, rt, gm);
+    } else {
+        if (!find_row_tile(p.tb, BM, tm, rt)) return;
+        gm.g[0] = gm.g[1] = gm.g[2] = gm.g[3] = rt.g;
+        gm.mixed = false;
+    }
+    const int j0 = tn * BN;                          // output columns are input features
+    const int cols_valid = min(BN, p.K - j0);
+    const int l = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wm = w & 1, wn = w >> 1;
+
+    f32x4 acc[TB][8];
+
+    const lora_bf16* dYt = p.dY + (int64_t)rt.row_start * p.N;
+    const lora_bf16* Wt = p.W + j0;
+    const uint32_t lds0 = lds_addr_of(smem);
+    const FragLanes16 fl = frag_lanes16<true>(wn);
+    const int tok_org = wm * (32 * MB) * 128, out_org = TILE_BYTES;      // (the wave's columns are in fl.col_off)
+    const SlabLanes sd = row_slab_lanes(p.N, rt.rows, 8), sw = col_slab16_lanes(p.K, BK, cols_valid);
+    const int nk = p.N / BK;
+    const int rr = LORA ? p.r : 16;
+    const lora_bf16* dSt = p.dS + (int64_t)rt.row_start * rr;
+    const lora_bf16* At = p.A + (int64_t)gm.g[0] * rr * p.K + j0;         // A of the tile's first adapter
+    const int lo = (nk & 1) * STAGE_BYTES;           // the stage that receives the LoRA slab pair
+    if (nk > 0) {
+        load_slab<2 * MB>(lds0, dYt + 0, sd);
+        load_slab(lds0 + TILE_BYTES, Wt, sw);
+    } else if (LORA) {
+        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sa = col_slab16_lanes(p.K, rr, cols_valid);
+        load_slab<2 * MB>(lds0, dSt, ss);
+        load_slab(lds0 + TILE_BYTES, At, sa);
+    }
+    zero_acc16<MB>(acc);                               // while the first slabs are on their way
+
+    // keep flags: state of the hash pieces, and what changes with the 16-row block row they work on
+    KeepShadow16 ks;
+    NoShadow none;
+    uint32_t keep_all = 0;
+    uint32_t* flags = (uint32_t*)(smem + GEMM_LDS_BYTES) + threadIdx.x;     // [2 * MB][NTHREADS]
+    const uint32_t cp0 = (uint32_t)(j0 + wn * 128 + 4 * (l >> 4)) >> 1;     // this lane's first column pair
+    auto keep_step_begin = [&](int kt) {
+        const int wd0 = kt * WPS, idx = wd0 & 15;
+        if (idx == 0) {
+            // next block row of the wave: its adapter's threshold and the row keys of its rows
+            const int blk = wm * (32 * MB) + (wd0 >> 4) * 16;
+            const int g = group_adapter(gm, blk >> 6);
+            const KeepThreshold kth = keep_threshold(p.tb.T[g]);
+            ks.tm1 = kth.tm1_packed;
+            keep_all = kth.keep_all;
+            const RowKey rk = row_key(p.tb.k0[g], p.tb.k1[g], (uint32_t)(rt.row_start - p.tb.row0[g] + blk + (l & 15)));
+            ks.x0 = rk.a + cp0 * kGold;
+            ks.rkb = rk.b;
+        }
+        ks.xoff = (uint32_t)((idx >> 1) * 8) * kGold;
+        ks.shift = (uint32_t)idx;
+    };
+    auto keep_step_end = [&](int kt) {
+        const int wd0 = kt * WPS;
+        if ((wd0 & 15) + WPS == 16) {
+            flags[(wd0 >> 4) * NTHREADS] = ks.fcur | keep_all;
+            ks.fcur = 0;
+        }
+    };
+    if (LORA) {
+        // defined from the start: the pieces also run in a step that forms nothing (see the last base slab)
+        ks.fcur = ks.x0 = ks.rkb = ks.xoff = ks.shift = ks.tm1 = ks.xb = ks.m4 = 0;
+        ks.x[0] = ks.x[1] = ks.t[0] = ks.t[1] = 0;
+    }
+
+    wait_slab_loads();
+    __syncthreads();
+    Frags16<MB> f;
+    if (nk > 0) read_frags16<true, MB>(f, smem + tok_org, smem + out_org, fl);
+    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
+    // slab steps 0 .. nk-2 bring the next base slab pair; the first 32 of all steps also carry the hash pieces
+    Pipe pp{(const char*)(dYt + BK), (const char*)(Wt + (int64_t)BK * p.K), BK * 2, (int64_t)BK * p.K * 2, 0u};
+    int kt = 0;
+    if constexpr (LORA) {
+        for (; kt < min(nk - 1, FLAG_STEPS); ++kt) {
+            keep_step_begin(kt);
+            slab_step16<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sd, sw, true, true, ks);
+            keep_step_end(kt);
+        }
+    }
+    for (; kt < nk - 1; ++kt)
+        slab_step16<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sd, sw, true, true, none);
+    if (nk > 0) {
+        // the last base slab: the LoRA slab pair [dS | A] rides in as one more slab (nothing if there is no
+        // LoRA term); its lane offsets are formed only now, the main loop has no registers for them
+        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sa = col_slab16_lanes(p.K, rr, cols_valid);
+        pp.src_tok = (const char*)dSt;
+        pp.src_out = (const char*)At;
+        if constexpr (LORA) {
+            // one code path for this step whatever kt is (two would have to merge all the accumulators):
+            // past the 32nd step the hash pieces still run, on a step number that is never flushed
+            const bool forming = kt < FLAG_STEPS;
+            if (forming) keep_step_begin(kt);
+            slab_step16<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sa, true, false, ks);
+            if (forming) keep_step_end(kt);
+        } else {
+            slab_step16<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sa, false, false, none);
+        }
+    }
+    if constexpr (LORA) {
+        // a contraction of fewer than 32 slabs has left flags to form: same pieces, on their own
+#pragma unroll 1
+        for (int kt = min(nk, FLAG_STEPS); kt < FLAG_STEPS; ++kt) {
+            keep_step_begin(kt);
+            keep_pieces_plain16<WPS>(ks);
+            keep_step_end(kt);
+        }
+    }
+    __syncthreads();                                  // every wave is done with the last base slab's stage
+    // The lane number is taken afresh and hidden from the optimiser: everything the way out derives from
+    // it (addresses, predicates) is then formed here instead of before the main loop, where it would
+    // occupy registers through all of it.
+    int le = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    asm volatile("" : "+v"(le));
+    const uint32_t* flags_e = (const uint32_t*)(smem + GEMM_LDS_BYTES) + w * 64 + le;
+    char* stage = smem + (STAGE_BYTES - lo) + w * 8192;               // in the stage the base product has left
+    const char* lds_tok = smem + lo + tok_org;
+    const char* lds_out = smem + lo + out_org;
+    const bool col_ok = wn * 128 + (le & 15) * 8 < cols_valid;
+    lora_bf16* out = p.dX + (int64_t)rt.row_start * p.K + j0 + wn * 128;
+    if constexpr (!LORA) {
+#pragma unroll
+        for (int bp = 0; bp < MB; ++bp) {
+            const int blk = wm * (32 * MB) + bp * 32;
+            block_store16<MB, false>(acc, bp, nullptr, nullptr, fl, 0, 0u, 0u, stage, out, p.K, blk, rt.rows - blk, col_ok, le);
+        }
+    } else {
+        // One run of 64-row groups per adapter present in the tile (a single run unless the tile is mixed).
+        const int nq = (rt.rows + 63) >> 6;
+        for (int q = 0; q < nq;) {
+            const int g = group_adapter(gm, q);
+            int qe = q + 1;
+            while (qe < nq && group_adapter(gm, qe) == g) ++qe;
+            if (q > 0) {                               // next adapter of a mixed tile: bring its A slab
+                __syncthreads();
+                const SlabLanes sa = col_slab16_lanes(p.K, rr, cols_valid);
+                load_slab(lds0 + lo + TILE_BYTES, p.A + (int64_t)g * rr * p.K + j0, sa);
+                wait_slab_loads();
+                __syncthreads();
+            }
+            const int rank_chunks = p.tb.rank[g] >> 3;
+#pragma unroll
+            for (int bp = 0; bp < MB; ++bp) {
+                const int blk = wm * (32 * MB) + bp * 32;          // first tile row of the pair
+                if (blk < 64 * q || blk >= 64 * qe) continue;
+                block_store16<MB, true>(acc, bp, lds_tok, lds_out, fl, rank_chunks, flags_e[(2 * bp) * NTHREADS],
+                                        flags_e[(2 * bp + 1) * NTHREADS], stage, out, p.K, blk, rt.rows - blk, col_ok, le);
             }
             q = qe;
         }
