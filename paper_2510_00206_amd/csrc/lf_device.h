@@ -258,9 +258,10 @@ __device__ __forceinline__ int row_slab_off(int row, int chunk) {
     return row * 128 + ((chunk ^ row_slab_swz(row)) << 4);
 }
 
-// GEMM column-operand slab: rows of 512 bytes (32 chunks), read with transposing loads, 32 lanes =
-// four consecutive rows x 64 bytes per cycle: the four rows go to different 64-byte windows.
-__device__ __forceinline__ int col_slab_swz(int row) { return (row & 3) << 2; }
+// GEMM column-operand slab: rows of 512 bytes (32 chunks), read with transposing loads for the 16x16x32 MFMA: the
+// 32 lanes served in one cycle address rows {a..a+3, a+8..a+11} x 32 bytes, which must fall into eight different
+// 32-byte windows: row bits (0, 1, 3) go to chunk bits (1, 2, 3).
+__device__ __forceinline__ int col_slab_swz(int row) { return ((row & 3) << 1) | (row & 8); }
 __device__ __forceinline__ int col_slab_off(int row, int chunk) {
     return row * 512 + ((chunk ^ col_slab_swz(row)) << 4);
 }
@@ -296,18 +297,6 @@ __device__ __forceinline__ int col_slab_tr_off(int r0, int c0, int i16) {
     const int row = r0 + (i16 >> 2);
     const int col = c0 + ((i16 & 3) << 2);
     return col_slab_off(row, col >> 3) + ((col & 7) << 1);
-}
-// ... in a GEMM column-operand slab read for the 16x16x32 MFMA: the 32 lanes served in one cycle address rows
-// {a..a+3, a+8..a+11} x 32 bytes, which must fall into eight different 32-byte windows: row bits (0, 1, 3) go to
-// chunk bits (1, 2, 3) ...
-__device__ __forceinline__ int col_slab16_swz(int row) { return ((row & 3) << 1) | (row & 8); }
-__device__ __forceinline__ int col_slab16_off(int row, int chunk) {
-    return row * 512 + ((chunk ^ col_slab16_swz(row)) << 4);
-}
-__device__ __forceinline__ int col_slab16_tr_off(int r0, int c0, int i16) {
-    const int row = r0 + (i16 >> 2);
-    const int col = c0 + ((i16 & 3) << 2);
-    return col_slab16_off(row, col >> 3) + ((col & 7) << 1);
 }
 // ... and in a streaming panel tile.
 __device__ __forceinline__ int panel_tr_off(int r0, int c0, int i16) {

@@ -5,9 +5,10 @@
 // with storage layouts X [M,K], W [N,K], S' [M,r], B [N,r], dY [M,N], dS [M,r], A [r,K].
 //
 // Both run a 256x256 output tile per workgroup: 4 waves, one per SIMD, each owning 128x128 of the
-// tile as 4x4 MFMA 32x32x16 bf16 blocks (256 fp32 accumulator registers; sixteen independent
-// accumulator chains per wave is what keeps the matrix pipe full on this chip).  A second
-// instantiation with 128 token rows per tile (2x4 blocks per wave) serves problems whose 256-row
+// tile as 8x8 MFMA 16x16x32 bf16 blocks (256 fp32 accumulator registers).  The chip is power-limited
+// under these kernels, and a register-resident loop of the 16x16x32 instruction sustains about 14 % more
+// than one of 32x32x16 (half the accumulator traffic per flop), which decides the block shape.  A second
+// instantiation with 128 token rows per tile (4x8 blocks per wave) serves problems whose 256-row
 // tiling would leave compute units without a tile.  64-deep operand
 // slabs are copied global -> LDS without passing through registers, double-buffered, and the
 // rank-r LoRA term rides as extra contraction steps on the same accumulators.  (2) contracts over
@@ -21,7 +22,7 @@
 
 namespace lf {
 
-constexpr int BN = 256, BK = 64;            // token rows per tile: 64 * MB (MB = 32-row blocks per wave: 4 or 2)
+constexpr int BN = 256, BK = 64;            // token rows per tile: 64 * MB (a wave owns 2 * MB blocks of 16 rows: MB = 4 or 2)
 constexpr int NTHREADS = 256;
 constexpr int NWAVES = NTHREADS / 64;
 constexpr int TILE_BYTES = BN * BK * 2;            // one 256x64 (or 64x256) bf16 slab: 32 KB (a 128-row token slab uses half)
@@ -88,20 +89,6 @@ __device__ __forceinline__ SlabLanes row_slab_lanes(int64_t ld, int rows_valid, 
     return s;
 }
 
-// Column-operand slab for (5): 64 contraction rows x 256 output columns, each row 32 chunks (512 B).
-// Wave w, pass i fills rows 2*(NWAVES*i + w), +1; lane l is (row l >> 5, physical chunk l & 31).
-__device__ __forceinline__ SlabLanes col_slab_lanes(int64_t ld, int rows_valid, int cols_valid) {
-    const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
-    SlabLanes s;
-#pragma unroll
-    for (int i = 0; i < PASSES; ++i) {
-        const int row = 2 * (NWAVES * i + w) + (l >> 5);
-        const int chunk = min((l & 31) ^ col_slab_swz(row), (cols_valid >> 3) - 1);
-        s.off[i] = (uint32_t)((min(row, rows_valid - 1) * ld + chunk * 8) * 2);
-    }
-    return s;
-}
-
 // Enqueue one slab (its first NP wave-passes: a 128-row token slab has 4): `src` is the
 // (workgroup-uniform) address of the slab's first element.
 template <int NP = PASSES>
@@ -112,70 +99,15 @@ __device__ __forceinline__ void load_slab(uint32_t lds_slab_addr, const lora_bf1
         copy16_to_lds((const char*)src, s.off[i], lds_slab_addr + i * (NWAVES * 1024) + wave);
 }
 
-// ---- fragment reads -----------------------------------------------------------------------------
-#define LF_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
-
-// Per-lane LDS offsets of the MFMA operand fragments.
-//  row slab: 32 tile rows x 16 contraction elements, lane l holds row (l & 31), elements
-//            8*(l >> 5) .. +7 of sub-step kk  -> row_off[kk] (+ 4096 bytes per 32 tile rows)
-//  col slab: 32 output columns x 16 contraction rows through two transposing reads, lane l holds
-//            column (l & 31), rows 16*kk + 8*(l >> 5) + {0..3 | 4..7} -> col_off[ni][half]
-//            (+ 8192 bytes per sub-step kk)
-struct FragLanes { int row_off[4]; int col_off[4][2]; };
-
-__device__ __forceinline__ FragLanes frag_lanes() {
-    const int l = threadIdx.x & 63;
-    FragLanes f;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) f.row_off[kk] = row_slab_off(l & 31, 2 * kk + (l >> 5));
-#pragma unroll
-    for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-            f.col_off[ni][h] = col_slab_tr_off(8 * (l >> 5) + 4 * h, ni * 32 + ((l >> 4) & 1) * 16, l & 15);
-    return f;
-}
-
-template <int MB> struct Frags { bf16x8 fo[4], ft[MB]; };
-
-// lds_tok / lds_out already include the wave's row (wm*128 rows) and column (wn*128) origin.
-// row_off_kk: fl.row_off[kk]; col_step: kk * 8192.
-template <bool OUT_IS_COL_SLAB, int MB>
-__device__ __forceinline__ void read_frags(Frags<MB>& f, const char* lds_tok, const char* lds_out,
-                                           const FragLanes& fl, int row_off_kk, int col_step) {
-#pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
-        if (OUT_IS_COL_SLAB) {
-            const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni][0] + col_step);
-            const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni][1] + col_step);
-            f.fo[ni] = join_tr(lo, hi);
-        } else {
-            f.fo[ni] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_out + row_off_kk + ni * 4096));
-        }
-    }
-#pragma unroll
-    for (int mi = 0; mi < MB; ++mi)
-        f.ft[mi] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_tok + row_off_kk + mi * 4096));
-}
-
-// An MFMA under wave-uniform control flow, issued from assembly with the accumulator tied to itself: with
+// ---- MFMAs issued from assembly ------------------------------------------------------------------
+// An MFMA under wave-uniform control flow is issued from assembly with the accumulator tied to itself: with
 // the builtin, the compiler may give the result another register block than its input and then pays for the
 // merge after the branch with copies of (and scratch space for) whole accumulator blocks.  The matrix pipe
 // interlocks a dependent MFMA on the same block by itself; what the compiler can no longer see is the
 // distance that any other reader of the block has to keep: mfma_in_place_done() supplies it after the last one.
-__device__ __forceinline__ void mfma_in_place(f32x16& c, bf16x8 a, bf16x8 b) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
-}
 __device__ __forceinline__ void mfma_in_place_done() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
 
-// MFMAs of all token-row blocks against all four output-column blocks.
-template <int MB>
-__device__ __forceinline__ void mma_frags(f32x16 (&acc)[MB][4], const Frags<MB>& f) {
-#pragma unroll
-    for (int mi = 0; mi < MB; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = LF_MFMA(f.fo[ni], f.ft[mi], acc[mi][ni]);
-}
+struct NoShadow {};        // a slab step without hash pieces
 
 // What the next slab pair is copied from: a token slab of 2*MB wave-passes and an out slab of PASSES.
 struct NextSlabs {
@@ -203,326 +135,10 @@ __device__ __forceinline__ void issue_copy(const NextSlabs& nx) {
     else copy16_to_lds(nx.src_out, nx.lanes_out.off[J - TOKP], nx.lds_out + (J - TOKP) * (NWAVES * 1024));
 }
 
-// One operand fragment read of the next sub-step.  Items come in the order the MFMAs need them
-// (MFMA slot s uses out fragment s & 3 and token fragment s >> 2): out0, tok0, out1, out2, out3,
-// tok1, tok2, tok3 (MB + 4 items).
-template <bool OUT_IS_COL_SLAB, int MB, int ITEM>
-__device__ __forceinline__ void read_frag_item(Frags<MB>& f, const char* lds_tok, const char* lds_out,
-                                               const FragLanes& fl, int row_off_kk, int col_step) {
-    constexpr bool is_tok = ITEM == 1 || ITEM >= 5;
-    constexpr int i = ITEM == 0 ? 0 : ITEM == 1 ? 0 : ITEM <= 4 ? ITEM - 1 : ITEM - 4;
-    if constexpr (is_tok) {
-        f.ft[i] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_tok + row_off_kk + i * 4096));
-    } else if constexpr (OUT_IS_COL_SLAB) {
-        const s16x4 lo = lds_read_tr(lds_out, fl.col_off[i][0] + col_step);
-        const s16x4 hi = lds_read_tr(lds_out, fl.col_off[i][1] + col_step);
-        f.fo[i] = join_tr(lo, hi);
-    } else {
-        f.fo[i] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_out + row_off_kk + i * 4096));
-    }
-}
-
-// ---- dropout keep flags formed in the shadow of the matrix work (operation (5)) ---------------------
-// Operation (5) needs keep(i, j) for every element of its output tile: 128 hash words per lane and
-// 256x256 tile.  The integer work is issued a few instructions at a time in MFMA slots that carry no
-// fragment read and no copy, where it runs while the matrix pipe is busy; each piece is one inline
-// assembly statement so that it stays in its slot.  A slab step forms WPS words (4 in a 256-row tile,
-// 2 in a 128-row tile), i.e. the flags of a tile are complete after 32 slab steps; sixteen words (32
-// elements: the low halves in bits 0..15, the high halves in bits 16..31) fill one flag register, which
-// is then parked in LDS until the epilogue.
-// Lane l of a wave owns, in 32x32 block (mi, ni), the elements 4*g4 + 2*pr + {0, 1} (g4 = 0..3, pr = 0..1) =
-// columns ni*32 + 8*g4 + 4*(l>>5) + 2*pr + {0, 1}: column pair cp0 + ni*16 + 4*g4 + pr with cp0 the lane's
-// first pair.  Word number wd = mi*32 + ni*8 + g4*2 + pr; flag register wd >> 4, bit wd & 15 (+16).
-struct KeepShadow {
-    uint32_t xb, x, t, m4, fcur;     // vector registers: running hash state, flags of the current register
-    uint32_t x0, rkb;                // row keys of the current 32-row block: rk.a + cp0 * kGold, rk.b
-    uint32_t xoff, shift, tm1;       // wave-uniform: pair offset * kGold and flag position of this step; packed T-1
-};
-struct NoShadow {};
-
-// Piece PID of a slab step: word J = PID >> 2, stage PID & 3 of
-//   x = x0 + pair*kGold;  x ^= x>>16;  | x *= M1; x += rk.b;  | x ^= x>>15; x *= M2;  | x ^= x>>16; flags
-template <int WPS, int PID>
-__device__ __forceinline__ void keep_piece(KeepShadow& k) {
-    constexpr int J = PID >> 2, ST = PID & 3;
-    constexpr uint32_t CJ = (uint32_t)((J >> 1) * 4 + (J & 1)) * kGold;      // pairs 0, 1, 4, 5 past the step's first
-    if constexpr (ST == 0 && J == 0) {
-        asm volatile("v_add_u32 %0, %4, %3\n\tv_lshrrev_b32 %1, 16, %0\n\tv_xor_b32 %2, %0, %1"
-                     : "=&v"(k.xb), "=&v"(k.t), "=&v"(k.x) : "v"(k.x0), "s"(k.xoff));
-    } else if constexpr (ST == 0) {
-        asm volatile("v_add_u32 %0, %3, %2\n\tv_lshrrev_b32 %1, 16, %0\n\tv_xor_b32 %0, %0, %1"
-                     : "=&v"(k.x), "=&v"(k.t) : "v"(k.xb), "s"(CJ));
-    } else if constexpr (ST == 1) {
-        asm volatile("v_mul_lo_u32 %0, %0, %2\n\tv_add_u32 %0, %0, %1" : "+v"(k.x) : "v"(k.rkb), "s"(kM1));
-    } else if constexpr (ST == 2) {
-        asm volatile("v_lshrrev_b32 %1, 15, %0\n\tv_xor_b32 %0, %0, %1\n\tv_mul_lo_u32 %0, %0, %2"
-                     : "+v"(k.x), "=&v"(k.t) : "s"(kM2));
-    } else {
-        // keep flag of a 16-bit half: min(saturating(bits - (T-1)), 1), both halves at once
-        if constexpr (J == 0)
-            asm volatile("v_lshrrev_b32 %1, 16, %0\n\tv_xor_b32 %0, %0, %1\n\tv_pk_sub_u16 %1, %0, %3 clamp\n\t"
-                         "v_pk_min_u16 %2, %1, %4"
-                         : "+v"(k.x), "=&v"(k.t), "=&v"(k.m4) : "s"(k.tm1), "s"(0x00010001u));
-        else
-            asm volatile("v_lshrrev_b32 %1, 16, %0\n\tv_xor_b32 %0, %0, %1\n\tv_pk_sub_u16 %1, %0, %3 clamp\n\t"
-                         "v_pk_min_u16 %1, %1, %4\n\tv_lshl_or_b32 %2, %1, %5, %2"
-                         : "+v"(k.x), "=&v"(k.t), "+v"(k.m4) : "s"(k.tm1), "s"(0x00010001u), "n"(J));
-        if constexpr (J == WPS - 1)
-            asm volatile("v_lshl_or_b32 %0, %1, %2, %0" : "+v"(k.fcur) : "v"(k.m4), "s"(k.shift));
-    }
-}
-
-// Which piece rides on MFMA slot S of sub-step SUB (-1: none): slots without a fragment read or a copy.
-constexpr int shadow_piece_of(int MB, int SUB, int S) {
-    if (MB == 4) return SUB == 2 && (S & 1) ? S >> 1 : SUB == 3 && S < 8 ? 8 + S : -1;
-    return SUB < 3 && S == 6 ? SUB : SUB == 3 && S < 4 ? 3 + S : SUB == 3 && S == 7 ? 7 : -1;
-}
-template <int MB, int SUB, int S> __device__ __forceinline__ void shadow_slot(NoShadow&) {}
-template <int MB, int SUB, int S> __device__ __forceinline__ void shadow_slot(KeepShadow& k) {
-    constexpr int pid = shadow_piece_of(MB, SUB, S);
-    if constexpr (pid >= 0) keep_piece<(MB == 4 ? 4 : 2), pid>(k);
-}
-// the same pieces outside any slab step (tiles with fewer than 32 slab steps)
-template <int WPS, int PID = 0>
-__device__ __forceinline__ void keep_pieces_plain(KeepShadow& k) {
-    if constexpr (PID < 4 * WPS) {
-        keep_piece<WPS, PID>(k);
-        keep_pieces_plain<WPS, PID + 1>(k);
-    }
-}
-
-// One sub-step: 4*MB MFMAs, each followed by at most one other instruction group (two in the 128-row
-// variant) - fragment reads of the next sub-step and global->LDS copies of the next slab pair - so that
-// every LDS read and every copy is issued while an MFMA executes (a copy or read issued between two
-// groups of MFMAs leaves the matrix pipe idle for its whole issue time).  With MB = 4 reads sit on
-// even slots and copies on odd ones; with MB = 2 the six reads sit on slots 0..5 and copies on odd slots.
-// MODE 0: reads of sub-step KK_NEXT + copies; MODE 1: MFMAs only; MODE 2: reads of the next slab's sub-step 0.
-template <bool OUT_IS_COL_SLAB, int MB, int SUB, int KK_NEXT, int COPY0, int COPIES, int SLOT0, int SLOT1, int MODE, class SH>
-__device__ __forceinline__ void phase_slots(f32x16 (&acc)[MB][4], const Frags<MB>& cur, Frags<MB>& nxt,
-                                            const char* lds_tok, const char* lds_out, const FragLanes& fl,
-                                            const NextSlabs& nx, SH& sh, Pipe& pp) {
-#define LF_SLOT(S)                                                                                        \
-    if constexpr ((S) >= SLOT0 && (S) < SLOT1 && (S) < 4 * MB) {                                         \
-        acc[(S) >> 2][(S) & 3] = LF_MFMA(cur.fo[(S) & 3], cur.ft[(S) >> 2], acc[(S) >> 2][(S) & 3]);      \
-        if constexpr (MODE == 2) {                                                                        \
-            /* hand-over half: all fragment reads of the next slab ride on the last 2*MB slots */       \
-            if (nx.valid) {                                                                               \
-                read_frag_item<OUT_IS_COL_SLAB, MB, ((S) - 2 * MB)>(nxt, lds_tok, lds_out, fl, fl.row_off[0], 0); \
-                if constexpr (MB == 2 && (S) < 6)                                                         \
-                    read_frag_item<OUT_IS_COL_SLAB, MB, (S)>(nxt, lds_tok, lds_out, fl, fl.row_off[0], 0);  \
-            }                                                                                             \
-        } else if constexpr (MODE == 1) {                                                                 \
-        } else if constexpr (MB == 4) {                                                                   \
-            if constexpr (((S) & 1) == 0)                                                                 \
-                read_frag_item<OUT_IS_COL_SLAB, MB, ((S) >> 1)>(nxt, lds_tok, lds_out, fl, fl.row_off[KK_NEXT], \
-                                                               KK_NEXT * 8192);                          \
-            else if constexpr (((S) >> 1) < COPIES)                                                       \
-                issue_copy<MB, (COPY0 + ((S) >> 1))>(nx);                                                   \
-        } else {                                                                                          \
-            if constexpr ((S) < MB + 4)                                                                   \
-                read_frag_item<OUT_IS_COL_SLAB, MB, (S)>(nxt, lds_tok, lds_out, fl, fl.row_off[KK_NEXT],   \
-                                                        KK_NEXT * 8192);                                 \
-            if constexpr (((S) & 1) == 1 && ((S) >> 1) < COPIES)                                          \
-                issue_copy<MB, (COPY0 + ((S) >> 1))>(nx);                                                   \
-        }                                                                                                 \
-        shadow_slot<MB, SUB, (S)>(sh);                                                                    \
-        if constexpr (MODE == 2 && (S) == 2 * MB) {                                                       \
-            /* every copy of this step has been issued: the sources move on to the slab pair after */   \
-            pp.src_tok += pp.adv_tok;                                                                     \
-            pp.src_out += pp.adv_out;                                                                     \
-        }                                                                                                 \
-        __builtin_amdgcn_sched_barrier(0);                                                                \
-    }
-    LF_SLOT(0) LF_SLOT(1) LF_SLOT(2) LF_SLOT(3) LF_SLOT(4) LF_SLOT(5) LF_SLOT(6) LF_SLOT(7)
-    LF_SLOT(8) LF_SLOT(9) LF_SLOT(10) LF_SLOT(11) LF_SLOT(12) LF_SLOT(13) LF_SLOT(14) LF_SLOT(15)
-#undef LF_SLOT
-}
-
-// One 64-deep slab pair: sub-steps 0..3, the copies of the next slab pair (16 spread over sub-steps
-// 0 and 1; 12 over sub-steps 0..2 in the 128-row variant), and in the middle of sub-step 3 the hand-over
-// (copies landed, workgroup barrier) followed by the first fragment reads of the next slab.  On entry
-// f0 holds the fragments of sub-step 0 of the current slab; on exit it holds those of the next slab.
-template <bool OUT_IS_COL_SLAB, int MB, class SH>
-__device__ __forceinline__ void slab_step(f32x16 (&acc)[MB][4], Frags<MB>& f0, Frags<MB>& f1, const char* lds_tok_org,
-                                          const char* lds_out_org, uint32_t lds_copy_org, const FragLanes& fl, Pipe& pp,
-                                          const SlabLanes& lanes_tok, const SlabLanes& lanes_out, bool copy_next, SH& sh) {
-    static_assert(PASSES == 8 && (MB == 4 || MB == 2), "copy schedule below assumes 8 + 2*MB copies per slab pair");
-    constexpr int NS = 4 * MB;
-    // lds_tok_org / lds_out_org: the wave's origin in the token / out slab of stage 0; lds_copy_org: LDS
-    // address of stage 0 plus this wave's 1024 bytes of every copy pass
-    const uint32_t nxt = STAGE_BYTES - pp.rd;
-    const char* cur_tok = lds_tok_org + pp.rd;
-    const char* cur_out = lds_out_org + pp.rd;
-    const NextSlabs nx{pp.src_tok, pp.src_out, lanes_tok, lanes_out, lds_copy_org + nxt, lds_copy_org + nxt + TILE_BYTES,
-                       copy_next};
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (MB == 4) {
-        phase_slots<OUT_IS_COL_SLAB, MB, 0, 1, 0, 8, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh, pp);   // copies 0..7
-        phase_slots<OUT_IS_COL_SLAB, MB, 1, 2, 8, 8, 0, NS, 0>(acc, f1, f0, cur_tok, cur_out, fl, nx, sh, pp);   // copies 8..15
-        phase_slots<OUT_IS_COL_SLAB, MB, 2, 3, 0, 0, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh, pp);
-    } else {
-        phase_slots<OUT_IS_COL_SLAB, MB, 0, 1, 0, 4, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh, pp);   // copies 0..3
-        phase_slots<OUT_IS_COL_SLAB, MB, 1, 2, 4, 4, 0, NS, 0>(acc, f1, f0, cur_tok, cur_out, fl, nx, sh, pp);   // copies 4..7
-        phase_slots<OUT_IS_COL_SLAB, MB, 2, 3, 8, 4, 0, NS, 0>(acc, f0, f1, cur_tok, cur_out, fl, nx, sh, pp);   // copies 8..11
-    }
-    // sub-step 3: first half, hand-over, second half with the next slab's first fragment reads
-    phase_slots<OUT_IS_COL_SLAB, MB, 3, 0, 0, 0, 0, NS / 2, 1>(acc, f1, f0, cur_tok, cur_out, fl, nx, sh, pp);
-    wait_slab_loads();
-    __syncthreads();
-    phase_slots<OUT_IS_COL_SLAB, MB, 3, 0, 0, 0, NS / 2, NS, 2>(acc, f1, f0, lds_tok_org + nxt, lds_out_org + nxt, fl, nx, sh, pp);
-    pp.rd = nxt;
-}
-
-// Accumulator element (mi, ni, i) of lane l is output row  wm*32*MB + mi*32 + (l & 31)  and output
-// column  wn*128 + ni*32 + 8*(i >> 2) + 4*(l >> 5) + (i & 3)  of the tile: a lane owns groups of four
-// consecutive columns of one row.  Storing those 8-byte groups directly would touch 32 different
-// rows per instruction; instead each wave transposes its (32*MB)x128 bf16 sub-tile through its own 32 KB
-// of the (now idle) slab LDS and writes whole 256-byte row segments, 16 bytes per lane.
-// LDS layout per wave: 32*MB rows x 32 eight-byte slots, slot index XOR-ed with (row & 31) so that the
-// 32 rows written by one instruction land in 32 different slots.
-template <int MB>
-__device__ __forceinline__ void store_tile(const f32x16 (&acc)[MB][4], lora_bf16* out, int64_t ld,
-                                           int row_start, int rows_valid, int col_start, int cols_valid,
-                                           int wm, int wn, char* smem) {
-    const int l = threadIdx.x & 63;
-    __syncthreads();                                   // every wave is done reading operand slabs
-    char* reg = smem + (threadIdx.x >> 6) * 32768;
-#pragma unroll
-    for (int mi = 0; mi < MB; ++mi) {
-        const int r = mi * 32 + (l & 31);
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const f32x16& a = acc[mi][ni];
-                u32x2 v;
-                v.x = pack_bf16x2(a[4 * g4 + 0], a[4 * g4 + 1]);
-                v.y = pack_bf16x2(a[4 * g4 + 2], a[4 * g4 + 3]);
-                const int slot = ni * 8 + 2 * g4 + (l >> 5);
-                *(u32x2*)(reg + r * 256 + ((slot ^ (r & 31)) << 3)) = v;
-            }
-    }
-    // LDS operations of one wave complete in order: the reads below see the writes above
-    const int j = l & 15;                              // 16-byte chunk of the row: columns 8j .. 8j+7
-    const bool col_ok = wn * 128 + j * 8 < cols_valid;
-#pragma unroll 8
-    for (int it = 0; it < 8 * MB; ++it) {
-        const int r = it * 4 + (l >> 4);
-        u32x4 v = *(const u32x4*)(reg + r * 256 + ((j ^ ((r & 31) >> 1)) << 4));
-        if (r & 1) v = u32x4{v.z, v.w, v.x, v.y};      // odd rows hold the two slots of a chunk swapped
-        const int row = wm * (32 * MB) + r;
-        if (col_ok && row < rows_valid)
-            // write-once output: a non-temporal store keeps it from displacing the operands (and the
-            // activations that the next kernels re-read) in the L2 and the memory-side cache
-            __builtin_nontemporal_store(v, (u32x4*)(out + (int64_t)(row_start + row) * ld + col_start + wn * 128 + j * 8));
-    }
-}
-
-template <int MB>
-__device__ __forceinline__ void zero_acc(f32x16 (&acc)[MB][4]) {
-#pragma unroll
-    for (int mi = 0; mi < MB; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
-    // pin the register writes here (callers place them between the issue of the first slab copies
-    // and the wait for them); otherwise they are sunk to the first use, after the wait
-#pragma unroll
-    for (int mi = 0; mi < MB; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) asm volatile("" : "+a"(acc[mi][ni]));
-}
-
 // gm.g[q] for a run-time q, as a scalar (wave-uniform) value
 __device__ __forceinline__ int group_adapter(const GroupMap& gm, int q) {
     const int g = q == 0 ? gm.g[0] : q == 1 ? gm.g[1] : q == 2 ? gm.g[2] : gm.g[3];
     return __builtin_amdgcn_readfirstlane(g);
-}
-
-// ---- the way out of a tile, one 32-row block of a wave's sub-tile at a time ---------------------------
-// Accumulator element (ni, i) of lane l in block row mi is tile row  wm*32*MB + mi*32 + (l & 31)  and tile
-// column  wn*128 + ni*32 + 8*(i >> 2) + 4*(l >> 5) + (i & 3): a lane owns groups of four consecutive columns
-// of one row.  Storing those 8-byte groups directly would touch 32 different rows per instruction;
-// instead the block's 32 x 128 bf16 go through 8 KB of LDS of the wave's own (`stage`: 32 rows x 32 eight-byte
-// slots, slot index XOR-ed with the row so that the 32 rows written by one instruction land in 32
-// different slots) and whole 256-byte row segments are stored, 16 bytes per lane, non-temporally: the
-// output is write-once, and keeping it out of the L2 and the memory-side cache leaves the operands (and the
-// activations that the next kernels re-read) there.
-// LORA (operation (5)): before rounding, the masked LoRA term of the block is added to the finished
-// base-gradient accumulators: t = dS A^T on a fresh accumulator per 32x32 block (dS arrives scaled by s*q),
-// t & flag, + acc.  lds_tok / lds_out: the LoRA slab pair (dS rows of this wave, A columns of this wave).
-// F0 / F1: keep flags of blocks (mi, 0..1) / (mi, 2..3), bit (ni & 1) * 8 + g4 * 2 + pr for element
-// 4*g4 + 2*pr, +16 for the next one.
-template <int MB, bool LORA>
-__device__ __forceinline__ void block_store(f32x16 (&acc)[4], int mi, const char* lds_tok, const char* lds_out,
-                                            const FragLanes& fl, int nkk, uint32_t F0, uint32_t F1, char* stage,
-                                            lora_bf16* out, int64_t ld, int row0_glob, int rows_left, bool col_ok,
-                                            int l) {
-    const int r = l & 31;
-    f32x16 t[4];
-    if constexpr (LORA) {
-        // t for the four 32x32 blocks of this block row, in vector registers (the accumulator registers all
-        // hold the tile): the MFMAs are issued from assembly with a vector destination, the first of each
-        // chain on a zero input, all of them back to back before the first result is touched
-#pragma unroll 1
-        for (int kk = 0; kk < nkk; ++kk) {
-            const bf16x8 ft = __builtin_bit_cast(
-                bf16x8, *(const u32x4*)(lds_tok + row_slab_off(l & 31, 2 * kk + (l >> 5)) + mi * 4096));
-            bf16x8 fo[4];
-#pragma unroll
-            for (int ni = 0; ni < 4; ++ni) {
-                const s16x4 lo = lds_read_tr(lds_out, fl.col_off[ni][0] + kk * 8192);
-                const s16x4 hi = lds_read_tr(lds_out, fl.col_off[ni][1] + kk * 8192);
-                fo[ni] = join_tr(lo, hi);
-            }
-#pragma unroll
-            for (int ni = 0; ni < 4; ++ni) {
-                if (kk == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(t[ni]) : "v"(fo[ni]), "v"(ft));
-                else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(t[ni]) : "v"(fo[ni]), "v"(ft));
-            }
-        }
-        // the compiler does not know that these were MFMAs: the distance the last result needs before the
-        // vector ALU may read it (at most 19 wait states on this chip) is put in by hand
-        asm volatile("s_nop 15\n\ts_nop 3" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]));
-    }
-#pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
-        // the block stays an accumulator block up to here (otherwise the whole tile is copied to vector
-        // registers ahead of time, which neither fit)
-        asm volatile("" : "+a"(acc[ni]));
-        const uint32_t F = ni < 2 ? F0 : F1;
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-            float v[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                v[e] = acc[ni][4 * g4 + e];
-                if constexpr (LORA) {
-                    const int bit = (ni & 1) * 8 + g4 * 2 + (e >> 1) + (e & 1) * 16;
-                    const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe((int)F, bit, 1);     // 0 or 0xFFFFFFFF
-                    const float te = t[ni][4 * g4 + e];  // (a copy: bit_cast of a vector element reads element 0)
-                    v[e] += __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, te) & m);
-                }
-            }
-            u32x2 o;
-            o.x = pack_bf16x2(v[0], v[1]);
-            o.y = pack_bf16x2(v[2], v[3]);
-            const int slot = ni * 8 + 2 * g4 + (l >> 5);
-            *(u32x2*)(stage + r * 256 + ((slot ^ r) << 3)) = o;
-        }
-    }
-    // LDS operations of one wave complete in order: the reads below see the writes above, and the next
-    // block's writes come after these reads
-    const int j = l & 15;
-#pragma unroll
-    for (int it = 0; it < 8; ++it) {
-        const int rr = it * 4 + (l >> 4);
-        u32x4 v = *(const u32x4*)(stage + rr * 256 + ((j ^ (rr >> 1)) << 4));
-        if (rr & 1) v = u32x4{v.z, v.w, v.x, v.y};       // odd rows hold the two slots of a chunk swapped
-        if (col_ok && rr < rows_left)
-            __builtin_nontemporal_store(v, (u32x4*)(out + (int64_t)(row0_glob + rr) * ld + j * 8));
-    }
 }
 
 // ---- tiles of a persistent workgroup ---------------------------------------------------------------
@@ -559,173 +175,32 @@ __device__ __forceinline__ TileCtx decode_tile(const AdapterTable& tb, int M, in
 constexpr int WAVE_EXTRA_BYTES = 8192;
 constexpr int GEMM_LDS_TOTAL = GEMM_LDS_BYTES + NWAVES * WAVE_EXTRA_BYTES;     // 160 KB: all of a compute unit's
 
-// ---- operation (2): Y = X W + S' B ---------------------------------------------------------------
-template <int MB>
-__global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel32(FwdGemmArgs p) {
-    constexpr int BM = 64 * MB;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    const int total = p.tiles_m * p.tiles_n;
-    int id = blockIdx.x;
-    TileCtx tc = decode_tile(p.tb, p.M, BM, p.uniform_tiles, p.tiles_m, p.tiles_n, id, p.N);
-    if (!tc.ok) return;
-    const int l = threadIdx.x & 63;
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wm = w & 1, wn = w >> 1;
-    const int nk = p.K / BK;
-    const uint32_t lds0 = lds_addr_of(smem);
-    const uint32_t wave_lds = w * 1024;
-    const FragLanes fl = frag_lanes();
-    const int tok_org = wm * (32 * MB) * 128, out_org = TILE_BYTES + wn * 128 * 128;
-    // p.r == 0 (no LoRA slab) and p.K == 0 (LoRA slab only) serve the unfused baseline's plain GEMMs.
-    const bool has_lora = p.r > 0;
-    const int rr = has_lora ? p.r : 16;
-    NoShadow none;
-    Pipe pp{nullptr, nullptr, BK * 2, BK * 2, 0u};
-
-    // first slab pair of the first tile
-    SlabLanes sx = row_slab_lanes(p.K, tc.rt.rows, 8), sw = row_slab_lanes(p.K, tc.cols_valid, 8);
-    if (nk > 0) {
-        load_slab<2 * MB>(lds0, p.X + (int64_t)tc.rt.row_start * p.K, sx);
-        load_slab(lds0 + TILE_BYTES, p.W + (int64_t)tc.c0 * p.K, sw);
-    }
-    for (;;) {
-        const RowTile rt = tc.rt;
-        const GroupMap gm = tc.gm;
-        const int n0 = tc.c0, cols_valid = tc.cols_valid;
-        const lora_bf16* Xt = p.X + (int64_t)rt.row_start * p.K;
-        const lora_bf16* Wt = p.W + (int64_t)n0 * p.K;
-        const lora_bf16* Ssrc = p.S + (int64_t)rt.row_start * p.r;
-        const lora_bf16* Bsrc = p.B + ((int64_t)rt.g * p.N + n0) * p.r;
-        if (nk == 0) {
-            const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
-            load_slab<2 * MB>(lds0 + pp.rd, Ssrc, ss);
-            load_slab(lds0 + pp.rd + TILE_BYTES, Bsrc, sb);
-        }
-        f32x16 acc[MB][4];
-        zero_acc(acc);                                 // while the first slabs are on their way (first tile)
-        wait_slab_loads();
-        __syncthreads();
-        Frags<MB> f0, f1;
-        read_frags<false>(f0, smem + pp.rd + tok_org, smem + pp.rd + out_org, fl, fl.row_off[0], 0);
-        pp.src_tok = (const char*)(Xt + BK);
-        pp.src_out = (const char*)(Wt + BK);
-        for (int kt = 0; kt + 1 < nk; ++kt)
-            slab_step<false, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sx, sw, true, none);
-        // the lane offsets of the LoRA slab pair are formed only now: through the main loop they would cost
-        // sixteen registers that it does not have
-        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
-        if (nk > 0) {
-            // after the last base slab the LoRA step rides as one more slab: token operand S' [rows, r],
-            // out operand B [N, r]
-            pp.src_tok = (const char*)Ssrc;
-            pp.src_out = (const char*)Bsrc;
-            slab_step<false, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sb,
-                                 has_lora && !gm.mixed, none);
-        }
-        const uint32_t lo = pp.rd;                     // the stage that holds (or receives) the LoRA slab pair
-
-        // The next tile of this workgroup: its first slab pair is asked for now, into the stage that the last
-        // base slab has just left, and arrives while the LoRA step and the way out run.  (The tile number is
-        // hidden from the optimiser, or everything derived from it would be formed - and kept in registers -
-        // before the main loop.)
-        int next = id + (int)gridDim.x;
-        asm volatile("" : "+s"(next));
-        const bool has_next = next < total;
-        if (has_next) {
-            tc = decode_tile(p.tb, p.M, BM, p.uniform_tiles, p.tiles_m, p.tiles_n, next, p.N);
-            sx = row_slab_lanes(p.K, tc.rt.rows, 8);
-            sw = row_slab_lanes(p.K, tc.cols_valid, 8);
-            if (nk > 0) {
-                load_slab<2 * MB>(lds0 + (STAGE_BYTES - lo), p.X + (int64_t)tc.rt.row_start * p.K, sx);
-                load_slab(lds0 + (STAGE_BYTES - lo) + TILE_BYTES, p.W + (int64_t)tc.c0 * p.K, sw);
-            }
-        }
-
-        if (has_lora) {
-            // One pass per adapter present in the tile: a single one unless the tile is mixed (FusedMultiLoRA
-            // with tiles cut uniformly over the packed batch: one adapter per 64-row group).  The slab pair of
-            // an unmixed tile has come in with the last base slab; a mixed tile loads the S' slab of the whole
-            // tile once and the B slab once per group.  A group's sub-steps go only to the 32-row blocks inside
-            // it, so that no value of one adapter ever meets a row of another - not even multiplied by zero.
-            const int ngroups = gm.mixed ? (rt.rows + 63) >> 6 : 1;
-#pragma unroll 1
-            for (int q = 0; q < ngroups; ++q) {
-                const int g = group_adapter(gm, q);
-                if (gm.mixed) {
-                    __syncthreads();                   // every wave is done with the stage's previous contents
-                    if (q == 0) load_slab<2 * MB>(lds0 + lo, Ssrc, ss);
-                    load_slab(lds0 + lo + TILE_BYTES, p.B + ((int64_t)g * p.N + n0) * p.r, sb);
-                    wait_slab_loads();                 // (also the next tile's first slab pair: mixed tiles are rare)
-                    __syncthreads();
-                }
-                const int blk_lo = gm.mixed ? 64 * q : 0, blk_hi = gm.mixed ? 64 * q + 64 : BM;
-                const int nkk = p.tb.rank[g] >> 4;
-#pragma unroll 1
-                for (int kk = 0; kk < nkk; ++kk) {
-                    Frags<MB> f;
-                    read_frags<false>(f, smem + lo + tok_org, smem + lo + out_org, fl, row_slab_off(l & 31, 2 * kk + (l >> 5)), 0);
-#pragma unroll
-                    for (int mi = 0; mi < MB; ++mi) {
-                        const int blk = wm * (32 * MB) + mi * 32;       // first tile row of the block
-                        if (blk < blk_lo || blk >= blk_hi) continue;
-#pragma unroll
-                        for (int ni = 0; ni < 4; ++ni) mfma_in_place(acc[mi][ni], f.fo[ni], f.ft[mi]);
-                    }
-                }
-            }
-            mfma_in_place_done();
-        }
-
-        // way out, block row by block row, through the wave's own 8 KB
-        {
-            int le = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-            asm volatile("" : "+v"(le));               // (derived values are formed here, not before the main loop)
-            char* stage = smem + GEMM_LDS_BYTES + w * WAVE_EXTRA_BYTES;
-            const bool col_ok = wn * 128 + (le & 15) * 8 < cols_valid;
-            lora_bf16* out = p.Y + (int64_t)rt.row_start * p.N + n0 + wn * 128;
-#pragma unroll
-            for (int mi = 0; mi < MB; ++mi) {
-                const int blk = wm * (32 * MB) + mi * 32;
-                block_store<MB, false>(acc[mi], mi, nullptr, nullptr, fl, 0, 0u, 0u, stage, out, p.N, blk, rt.rows - blk,
-                                       col_ok, le);
-            }
-        }
-        if (!has_next) break;
-        id = next;
-        pp.rd = STAGE_BYTES - lo;
-    }
-}
-
-// ======================================================================================================
-// The same two kernels on the 16x16x32 MFMA.  The chip is power-limited under these kernels, and a
-// register-resident loop of v_mfma_f32_16x16x32_bf16 sustains about 14 % more than one of the 32x32x16
-// instruction (half the accumulator traffic per flop): a wave's 128x128 sub-tile is 8x8 blocks of 16x16,
-// a 64-deep slab two sub-steps of 64 MFMAs.
-// ======================================================================================================
-#define LF_MFMA16X(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_bf16((a), (b), (c), 0, 0, 0)
+// ---- fragments and the MFMA --------------------------------------------------------------------------
+#define LF_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_bf16((a), (b), (c), 0, 0, 0)
 
 // Per-lane LDS offsets of the operand fragments (16 rows or columns x 32 contraction elements per fragment;
 // lane l holds row or column l & 15, contraction elements 8 * (l >> 4) .. +7 of the sub-step).
 //  row slab: one 16-byte read at row_off[sub-step] + 2048 bytes per 16-row block;
 //  col slab (operation (5)): two transposing reads, contraction rows 32*sub + 8*(l >> 4) + {0..3 | 4..7}, at
 //            (col_off ^ (block << 5)) + 16384 * sub {+ 2048}.
-struct FragLanes16 { int row_off[2]; int col_off; };
+struct FragLanes { int row_off[2]; int col_off; };
 
 template <bool COL_SLAB>
-__device__ __forceinline__ FragLanes16 frag_lanes16(int wn) {
+__device__ __forceinline__ FragLanes frag_lanes(int wn) {
     const int l = threadIdx.x & 63;
-    FragLanes16 f;
+    FragLanes f;
     f.row_off[0] = row_slab_off(l & 15, l >> 4);
     f.row_off[1] = row_slab_off(l & 15, 4 + (l >> 4));
-    f.col_off = COL_SLAB ? col_slab16_tr_off(8 * (l >> 4), wn * 128, l & 15) : 0;
+    f.col_off = COL_SLAB ? col_slab_tr_off(8 * (l >> 4), wn * 128, l & 15) : 0;
     return f;
 }
 
 // Fragments of a wave: the out operand double-buffered by sub-step, the token operand in place (block mi is
 // reloaded for the next sub-step as soon as the eight MFMAs of its row have been issued).
-template <int MB> struct Frags16 { bf16x8 fo[2][8]; bf16x8 ft[2 * MB]; };
+template <int MB> struct Frags { bf16x8 fo[2][8]; bf16x8 ft[2 * MB]; };
 
 template <bool COL_SLAB>
-__device__ __forceinline__ bf16x8 read_out_frag16(const char* lds_out, const FragLanes16& fl, int blk, int sub) {
+__device__ __forceinline__ bf16x8 read_out_frag(const char* lds_out, const FragLanes& fl, int blk, int sub) {
     if constexpr (COL_SLAB) {
         const int off = (fl.col_off ^ (blk << 5)) + sub * 16384;
         const s16x4 lo = lds_read_tr(lds_out, off);
@@ -735,21 +210,21 @@ __device__ __forceinline__ bf16x8 read_out_frag16(const char* lds_out, const Fra
         return __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_out + fl.row_off[sub] + blk * 2048));
     }
 }
-__device__ __forceinline__ bf16x8 read_tok_frag16(const char* lds_tok, const FragLanes16& fl, int blk, int sub) {
+__device__ __forceinline__ bf16x8 read_tok_frag(const char* lds_tok, const FragLanes& fl, int blk, int sub) {
     return __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_tok + fl.row_off[sub] + blk * 2048));
 }
 
 // all fragments of sub-step 0 of a slab (start of a tile)
 template <bool COL_SLAB, int MB>
-__device__ __forceinline__ void read_frags16(Frags16<MB>& f, const char* lds_tok, const char* lds_out, const FragLanes16& fl) {
+__device__ __forceinline__ void read_frags(Frags<MB>& f, const char* lds_tok, const char* lds_out, const FragLanes& fl) {
 #pragma unroll
-    for (int k = 0; k < 8; ++k) f.fo[0][k] = read_out_frag16<COL_SLAB>(lds_out, fl, k, 0);
+    for (int k = 0; k < 8; ++k) f.fo[0][k] = read_out_frag<COL_SLAB>(lds_out, fl, k, 0);
 #pragma unroll
-    for (int mi = 0; mi < 2 * MB; ++mi) f.ft[mi] = read_tok_frag16(lds_tok, fl, mi, 0);
+    for (int mi = 0; mi < 2 * MB; ++mi) f.ft[mi] = read_tok_frag(lds_tok, fl, mi, 0);
 }
 
 // What rides on MFMA slot s of sub-step `sub` (s = 8 * token block + out block; -1: nothing).
-template <int MB> struct Sched16 {
+template <int MB> struct Sched {
     static constexpr int TB = 2 * MB, SS = 8 * TB;
     static constexpr int HO = MB == 4 ? 36 : 14;          // sub-step 1: hand-over after this slot
     // read of out fragment k for the next sub-step (sub-step 0: of this slab; sub-step 1: of the next slab)
@@ -778,7 +253,7 @@ template <int MB> struct Sched16 {
 };
 
 // (operation (5) hangs its hash pieces on free slots; nothing for the others)
-template <int MB, int SUB, int S> __device__ __forceinline__ void shadow_slot16(NoShadow&) {}
+template <int MB, int SUB, int S> __device__ __forceinline__ void shadow_slot(NoShadow&) {}
 
 // LDS side of one slab step: where the current slab pair lies and where the next one goes.
 struct StepLds {
@@ -787,25 +262,25 @@ struct StepLds {
 };
 
 template <bool COL_SLAB, int MB, int S, class SH>
-__device__ __forceinline__ void slots16(f32x4 (&acc)[2 * MB][8], Frags16<MB>& f, const StepLds& L, const FragLanes16& fl,
+__device__ __forceinline__ void slots(f32x4 (&acc)[2 * MB][8], Frags<MB>& f, const StepLds& L, const FragLanes& fl,
                                         const NextSlabs& nx, bool read_next, SH& sh, Pipe& pp) {
-    using SC = Sched16<MB>;
+    using SC = Sched<MB>;
     constexpr int sub = S / SC::SS, s = S % SC::SS, mi = s >> 3, ni = s & 7;
-    acc[mi][ni] = LF_MFMA16X(f.fo[sub][ni], f.ft[mi], acc[mi][ni]);
+    acc[mi][ni] = LF_MFMA(f.fo[sub][ni], f.ft[mi], acc[mi][ni]);
     constexpr int k = SC::fo_read(sub, s);
     if constexpr (k >= 0) {
-        if constexpr (sub == 0) f.fo[1][k] = read_out_frag16<COL_SLAB>(L.cur_out, fl, k, 1);
-        else if (read_next) f.fo[0][k] = read_out_frag16<COL_SLAB>(L.nxt_out, fl, k, 0);
+        if constexpr (sub == 0) f.fo[1][k] = read_out_frag<COL_SLAB>(L.cur_out, fl, k, 1);
+        else if (read_next) f.fo[0][k] = read_out_frag<COL_SLAB>(L.nxt_out, fl, k, 0);
     }
     constexpr int m = SC::ft_read(sub, s);
     if constexpr (m >= 0) {
-        if constexpr (s == 1) f.ft[m] = read_tok_frag16(L.cur_tok, fl, m, sub);
-        else if constexpr (sub == 0) f.ft[m] = read_tok_frag16(L.cur_tok, fl, m, 1);
-        else if (read_next) f.ft[m] = read_tok_frag16(L.nxt_tok, fl, m, 0);
+        if constexpr (s == 1) f.ft[m] = read_tok_frag(L.cur_tok, fl, m, sub);
+        else if constexpr (sub == 0) f.ft[m] = read_tok_frag(L.cur_tok, fl, m, 1);
+        else if (read_next) f.ft[m] = read_tok_frag(L.nxt_tok, fl, m, 0);
     }
     constexpr int j = SC::copy_at(sub, s);
     if constexpr (j >= 0) issue_copy<MB, j>(nx);
-    shadow_slot16<MB, sub, s>(sh);
+    shadow_slot<MB, sub, s>(sh);
     if constexpr (sub == 1 && s == 0) {
         // every copy of this step has been issued: the sources move on to the slab pair after
         pp.src_tok += pp.adv_tok;
@@ -816,15 +291,15 @@ __device__ __forceinline__ void slots16(f32x4 (&acc)[2 * MB][8], Frags16<MB>& f,
         wait_slab_loads();
         __syncthreads();
     }
-    if constexpr (S + 1 < 2 * SC::SS) slots16<COL_SLAB, MB, S + 1>(acc, f, L, fl, nx, read_next, sh, pp);
+    if constexpr (S + 1 < 2 * SC::SS) slots<COL_SLAB, MB, S + 1>(acc, f, L, fl, nx, read_next, sh, pp);
 }
 
 // One 64-deep slab pair: two sub-steps of 16*MB MFMAs; the copies of the next slab pair ride on sub-step 0,
 // the hand-over (copies landed, workgroup barrier) sits in sub-step 1 and is followed by the first fragment
 // reads of the next slab (if read_next).  On entry f holds the fragments of sub-step 0 of the current slab.
 template <bool COL_SLAB, int MB, class SH>
-__device__ __forceinline__ void slab_step16(f32x4 (&acc)[2 * MB][8], Frags16<MB>& f, const char* lds_tok_org,
-                                            const char* lds_out_org, uint32_t lds_copy_org, const FragLanes16& fl, Pipe& pp,
+__device__ __forceinline__ void slab_step(f32x4 (&acc)[2 * MB][8], Frags<MB>& f, const char* lds_tok_org,
+                                            const char* lds_out_org, uint32_t lds_copy_org, const FragLanes& fl, Pipe& pp,
                                             const SlabLanes& lanes_tok, const SlabLanes& lanes_out, bool copy_next,
                                             bool read_next, SH& sh) {
     const uint32_t nxt = STAGE_BYTES - pp.rd;
@@ -832,12 +307,12 @@ __device__ __forceinline__ void slab_step16(f32x4 (&acc)[2 * MB][8], Frags16<MB>
     const NextSlabs nx{pp.src_tok, pp.src_out, lanes_tok, lanes_out, lds_copy_org + nxt, lds_copy_org + nxt + TILE_BYTES,
                        copy_next};
     __builtin_amdgcn_sched_barrier(0);
-    slots16<COL_SLAB, MB, 0>(acc, f, L, fl, nx, read_next, sh, pp);
+    slots<COL_SLAB, MB, 0>(acc, f, L, fl, nx, read_next, sh, pp);
     pp.rd = nxt;
 }
 
 template <int MB>
-__device__ __forceinline__ void zero_acc16(f32x4 (&acc)[2 * MB][8]) {
+__device__ __forceinline__ void zero_acc(f32x4 (&acc)[2 * MB][8]) {
 #pragma unroll
     for (int mi = 0; mi < 2 * MB; ++mi)
 #pragma unroll
@@ -849,11 +324,11 @@ __device__ __forceinline__ void zero_acc16(f32x4 (&acc)[2 * MB][8]) {
         for (int ni = 0; ni < 8; ++ni) asm volatile("" : "+a"(acc[mi][ni]));
 }
 
-// An MFMA under wave-uniform control flow with the accumulator tied to itself (see mfma_in_place).  Its
+// An MFMA under wave-uniform control flow with the accumulator tied to itself (see above).  Its
 // operands may have been written by the vector ALU just before (zero_past_rank): the compiler keeps the
 // distance an MFMA needs from such a write for its own MFMAs, not for one inside an assembly statement, so
 // the two wait states are part of the statement.
-__device__ __forceinline__ void mfma16_in_place(f32x4& c, bf16x8 a, bf16x8 b) {
+__device__ __forceinline__ void mfma_in_place(f32x4& c, bf16x8 a, bf16x8 b) {
     asm volatile("s_nop 1\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 
@@ -876,8 +351,8 @@ __device__ __forceinline__ bf16x8 zero_past_rank(bf16x8 v, int chunk, int valid_
 // accumulators: t = dS A^T per 16x16 block by MFMAs with a vector-register destination (dS arrives scaled by
 // s*q), t & flag, + acc.  F[h]: keep flags of block row 2*bp + h, bit ni*2 + pr for element 2*pr, +16 for 2*pr+1.
 template <int MB, bool LORA>
-__device__ __forceinline__ void block_store16(f32x4 (&acc)[2 * MB][8], int bp, const char* lds_tok, const char* lds_out,
-                                              const FragLanes16& fl, int rank_chunks, uint32_t F0, uint32_t F1, char* stage,
+__device__ __forceinline__ void block_store(f32x4 (&acc)[2 * MB][8], int bp, const char* lds_tok, const char* lds_out,
+                                              const FragLanes& fl, int rank_chunks, uint32_t F0, uint32_t F1, char* stage,
                                               lora_bf16* out, int64_t ld, int row0_glob, int rows_left, bool col_ok,
                                               int l) {
     f32x4 t[2][8];
@@ -901,7 +376,7 @@ __device__ __forceinline__ void block_store16(f32x4 (&acc)[2 * MB][8], int bp, c
             for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int ni = 0; ni < 8; ++ni) {
-                    // (s_nop 1: the operands may come straight from the vector ALU, see mfma16_in_place)
+                    // (s_nop 1: the operands may come straight from the vector ALU, see mfma_in_place)
                     if (kk == 0) asm volatile("s_nop 1\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=&v"(t[h][ni]) : "v"(fo[ni]), "v"(ft[h]));
                     else asm volatile("s_nop 1\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(t[h][ni]) : "v"(fo[ni]), "v"(ft[h]));
                 }
@@ -965,7 +440,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     const int nk = p.K / BK;
     const uint32_t lds0 = lds_addr_of(smem);
     const uint32_t wave_lds = w * 1024;
-    const FragLanes16 fl = frag_lanes16<false>(wn);
+    const FragLanes fl = frag_lanes<false>(wn);
     const int tok_org = wm * (32 * MB) * 128, out_org = TILE_BYTES + wn * 128 * 128;
     // p.r == 0 (no LoRA slab) and p.K == 0 (LoRA slab only) serve the unfused baseline's plain GEMMs.
     const bool has_lora = p.r > 0;
@@ -993,15 +468,15 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
             load_slab(lds0 + pp.rd + TILE_BYTES, Bsrc, sb);
         }
         f32x4 acc[TB][8];
-        zero_acc16<MB>(acc);                           // while the first slabs are on their way (first tile)
+        zero_acc<MB>(acc);                           // while the first slabs are on their way (first tile)
         wait_slab_loads();
         __syncthreads();
-        Frags16<MB> f;
-        if (nk > 0) read_frags16<false, MB>(f, smem + pp.rd + tok_org, smem + pp.rd + out_org, fl);
+        Frags<MB> f;
+        if (nk > 0) read_frags<false, MB>(f, smem + pp.rd + tok_org, smem + pp.rd + out_org, fl);
         pp.src_tok = (const char*)(Xt + BK);
         pp.src_out = (const char*)(Wt + BK);
         for (int kt = 0; kt + 1 < nk; ++kt)
-            slab_step16<false, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sx, sw, true, true, none);
+            slab_step<false, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sx, sw, true, true, none);
         // the lane offsets of the LoRA slab pair are formed only now: through the main loop they would cost
         // sixteen registers that it does not have
         const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
@@ -1010,7 +485,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
             // out operand B [N, r]
             pp.src_tok = (const char*)Ssrc;
             pp.src_out = (const char*)Bsrc;
-            slab_step16<false, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sb,
+            slab_step<false, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sb,
                                    has_lora && !gm.mixed, false, none);
         }
         const uint32_t lo = pp.rd;                     // the stage that holds (or receives) the LoRA slab pair
@@ -1067,7 +542,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
                         const bf16x8 ft = zero_past_rank(
                             __builtin_bit_cast(bf16x8, *(const u32x4*)(smem + lo + tok_org + off + mi * 2048)), chunk, rank_chunks);
 #pragma unroll
-                        for (int ni = 0; ni < 8; ++ni) mfma16_in_place(acc[mi][ni], fo[ni], ft);
+                        for (int ni = 0; ni < 8; ++ni) mfma_in_place(acc[mi][ni], fo[ni], ft);
                     }
                 }
             }
@@ -1084,7 +559,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
 #pragma unroll
             for (int bp = 0; bp < MB; ++bp) {
                 const int blk = wm * (32 * MB) + bp * 32;
-                block_store16<MB, false>(acc, bp, nullptr, nullptr, fl, 0, 0u, 0u, stage, out, p.N, blk, rt.rows - blk,
+                block_store<MB, false>(acc, bp, nullptr, nullptr, fl, 0, 0u, 0u, stage, out, p.N, blk, rt.rows - blk,
                                          col_ok, le);
             }
         }
@@ -1094,173 +569,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     }
 }
 
-// ---- operation (5): dX = dY W^T + mask*q*(dS A^T) ------------------------------------------------
-// LORA = false: the plain product dX = dY W^T (frozen linear, unfused baseline).  LORA = true: the base
-// product first, while the keep flags of the tile are formed in the shadow of its MFMAs; the LoRA slab
-// pair [dS | A] rides in as one more slab during the last base slab, and the masked LoRA term is added
-// block by block on the way out.  p.N == 0 (LoRA term only) serves the unfused baseline.
-template <int MB, bool LORA>
-__global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel32(DxGemmArgs p) {
-    constexpr int BM = 64 * MB;
-    constexpr int WPS = MB == 4 ? 4 : 2;             // hash words per slab step and lane
-    constexpr int FLAG_STEPS = 32 * MB / WPS;        // slab steps until the tile's flags are complete: 32
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    int tm, tn;
-    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
-    RowTile rt;
-    GroupMap gm;
-    if (p.uniform_tiles) {
-        find_uniform_tile(p.tb, p.M, BM, tm, rt, gm);
-    } else {
-        if (!find_row_tile(p.tb, BM, tm, rt)) return;
-        gm.g[0] = gm.g[1] = gm.g[2] = gm.g[3] = rt.g;
-        gm.mixed = false;
-    }
-    const int j0 = tn * BN;                          // output columns are input features
-    const int cols_valid = min(BN, p.K - j0);
-    const int l = threadIdx.x & 63;
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wm = w & 1, wn = w >> 1;
-
-    f32x16 acc[MB][4];
-
-    const lora_bf16* dYt = p.dY + (int64_t)rt.row_start * p.N;
-    const lora_bf16* Wt = p.W + j0;
-    const uint32_t lds0 = lds_addr_of(smem);
-    const FragLanes fl = frag_lanes();
-    const int tok_org = wm * (32 * MB) * 128, out_org = TILE_BYTES + wn * 128 * 2;
-    const SlabLanes sd = row_slab_lanes(p.N, rt.rows, 8), sw = col_slab_lanes(p.K, BK, cols_valid);
-    const int nk = p.N / BK;
-    const int rr = LORA ? p.r : 16;
-    const lora_bf16* dSt = p.dS + (int64_t)rt.row_start * rr;
-    const lora_bf16* At = p.A + (int64_t)gm.g[0] * rr * p.K + j0;         // A of the tile's first adapter
-    const int lo = (nk & 1) * STAGE_BYTES;           // the stage that receives the LoRA slab pair
-    if (nk > 0) {
-        load_slab<2 * MB>(lds0, dYt + 0, sd);
-        load_slab(lds0 + TILE_BYTES, Wt, sw);
-    } else if (LORA) {
-        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sa = col_slab_lanes(p.K, rr, cols_valid);
-        load_slab<2 * MB>(lds0, dSt, ss);
-        load_slab(lds0 + TILE_BYTES, At, sa);
-    }
-    zero_acc(acc);                                     // while the first slabs are on their way
-
-    // keep flags: state of the hash pieces, and what changes with the 32-row block they work on
-    KeepShadow ks;
-    NoShadow none;
-    uint32_t keep_all = 0;
-    uint32_t* flags = (uint32_t*)(smem + GEMM_LDS_BYTES) + threadIdx.x;     // [2 * MB][NTHREADS]
-    const uint32_t cp0 = (uint32_t)(j0 + wn * 128 + 4 * (l >> 5)) >> 1;     // this lane's first column pair
-    auto keep_step_begin = [&](int kt) {
-        const int wd0 = kt * WPS, idx = wd0 & 31;
-        if (idx == 0) {
-            // next 32-row block of the wave: its adapter's threshold and the row keys of its rows
-            const int blk = wm * (32 * MB) + (wd0 >> 5) * 32;
-            const int g = group_adapter(gm, blk >> 6);
-            const KeepThreshold kth = keep_threshold(p.tb.T[g]);
-            ks.tm1 = kth.tm1_packed;
-            keep_all = kth.keep_all;
-            const RowKey rk = row_key(p.tb.k0[g], p.tb.k1[g], (uint32_t)(rt.row_start - p.tb.row0[g] + blk + (l & 31)));
-            ks.x0 = rk.a + cp0 * kGold;
-            ks.rkb = rk.b;
-        }
-        ks.xoff = (uint32_t)((idx >> 3) * 16 + ((idx >> 1) & 3) * 4) * kGold;
-        ks.shift = (uint32_t)(wd0 & 15);
-    };
-    auto keep_step_end = [&](int kt) {
-        const int wd0 = kt * WPS;
-        if ((wd0 & 15) + WPS == 16) {
-            flags[(wd0 >> 4) * NTHREADS] = ks.fcur | keep_all;
-            ks.fcur = 0;
-        }
-    };
-    if (LORA) {
-        // defined from the start: the pieces also run in a step that forms nothing (see the last base slab)
-        ks.fcur = ks.x0 = ks.rkb = ks.xoff = ks.shift = ks.tm1 = 0;
-    }
-
-    wait_slab_loads();
-    __syncthreads();
-    Frags<MB> f0, f1;
-    if (nk > 0) read_frags<true>(f0, smem + tok_org, smem + out_org, fl, fl.row_off[0], 0);
-    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
-    // slab steps 0 .. nk-2 bring the next base slab pair; the first 32 of all steps also carry the hash pieces
-    Pipe pp{(const char*)(dYt + BK), (const char*)(Wt + (int64_t)BK * p.K), BK * 2, (int64_t)BK * p.K * 2, 0u};
-    int kt = 0;
-    if constexpr (LORA) {
-        for (; kt < min(nk - 1, FLAG_STEPS); ++kt) {
-            keep_step_begin(kt);
-            slab_step<true, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sd, sw, true, ks);
-            keep_step_end(kt);
-        }
-    }
-    for (; kt < nk - 1; ++kt)
-        slab_step<true, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sd, sw, true, none);
-    if (nk > 0) {
-        // the last base slab: the LoRA slab pair [dS | A] rides in as one more slab (nothing if there is no
-        // LoRA term); its lane offsets are formed only now, the main loop has no registers for them
-        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sa = col_slab_lanes(p.K, rr, cols_valid);
-        pp.src_tok = (const char*)dSt;
-        pp.src_out = (const char*)At;
-        if constexpr (LORA) {
-            // one code path for this step whatever kt is (two would have to merge all the accumulators):
-            // past the 32nd step the hash pieces still run, on a step number that is never flushed
-            const bool forming = kt < FLAG_STEPS;
-            if (forming) keep_step_begin(kt);
-            slab_step<true, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sa, true, ks);
-            if (forming) keep_step_end(kt);
-        } else {
-            slab_step<true, MB>(acc, f0, f1, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sa, false, none);
-        }
-    }
-    if constexpr (!LORA) {
-        store_tile(acc, p.dX, p.K, rt.row_start, rt.rows, j0, cols_valid, wm, wn, smem);
-    } else {
-        // a contraction of fewer than 32 slabs has left flags to form: same pieces, on their own
-#pragma unroll 1
-        for (int kt = min(nk, FLAG_STEPS); kt < FLAG_STEPS; ++kt) {
-            keep_step_begin(kt);
-            keep_pieces_plain<WPS>(ks);
-            keep_step_end(kt);
-        }
-        __syncthreads();                              // every wave is done with the last base slab's stage
-        // The lane number is taken afresh and hidden from the optimiser: everything the way out derives from
-        // it (addresses, predicates) is then formed here instead of before the main loop, where it would
-        // occupy registers through all of it.
-        int le = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-        asm volatile("" : "+v"(le));
-        const uint32_t* flags_e = (const uint32_t*)(smem + GEMM_LDS_BYTES) + w * 64 + le;
-        // One run of 64-row groups per adapter present in the tile (a single run unless the tile is mixed).
-        char* stage = smem + (STAGE_BYTES - lo) + w * 8192;
-        const char* lds_tok = smem + lo + tok_org;
-        const char* lds_out = smem + lo + out_org;
-        const bool col_ok = wn * 128 + (le & 15) * 8 < cols_valid;
-        lora_bf16* out = p.dX + (int64_t)rt.row_start * p.K + j0 + wn * 128;
-        const int nq = (rt.rows + 63) >> 6;
-        for (int q = 0; q < nq;) {
-            const int g = group_adapter(gm, q);
-            int qe = q + 1;
-            while (qe < nq && group_adapter(gm, qe) == g) ++qe;
-            if (q > 0) {                               // next adapter of a mixed tile: bring its A slab
-                __syncthreads();
-                const SlabLanes sa = col_slab_lanes(p.K, rr, cols_valid);
-                load_slab(lds0 + lo + TILE_BYTES, p.A + (int64_t)g * rr * p.K + j0, sa);
-                wait_slab_loads();
-                __syncthreads();
-            }
-            const int nkk = p.tb.rank[g] >> 4;
-#pragma unroll
-            for (int mi = 0; mi < MB; ++mi) {
-                const int blk = wm * (32 * MB) + mi * 32;          // first tile row of the block
-                if (blk < 64 * q || blk >= 64 * qe) continue;
-                block_store<MB, true>(acc[mi], mi, lds_tok, lds_out, fl, nkk, flags_e[(2 * mi) * NTHREADS],
-                                     flags_e[(2 * mi + 1) * NTHREADS], stage, out, p.K, blk, rt.rows - blk, col_ok, le);
-            }
-            q = qe;
-        }
-    }
-}
-
-// ---- dropout keep flags formed in the shadow of the matrix work (operation (5)), 16x16 blocks --------
+// ---- dropout keep flags formed in the shadow of the matrix work (operation (5)) ---------------------
 // Lane l of a wave owns, in 16x16 block (mi, ni), columns ni*16 + 4*(l >> 4) + {0..3} of tile row mi*16 + (l & 15):
 // column pairs cp0 + ni*8 + {0, 1} with cp0 the lane's first pair.  Word number of a block row wd = ni*2 + pr; one
 // flag register per block row, bit wd for the even column and bit wd + 16 for the odd one.  A slab step forms WPS
@@ -1268,7 +577,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel32(DxGemmArgs p) {
 // The MFMA here takes 16 cycles, so a piece is at most three full-rate instructions or one 32-bit multiply
 // (16 cycles by itself); the words of a step go through the six stages two at a time, alternating, so that a
 // piece never waits for the multiply before it.
-struct KeepShadow16 {
+struct KeepShadow {
     uint32_t xb, x[2], t[2], m4, fcur;     // vector registers: running hash state, flags of the current register
     uint32_t x0, rkb;                      // row keys of the current block row: rk.a + cp0 * kGold, rk.b
     uint32_t xoff, shift, tm1;             // wave-uniform: pair offset * kGold and flag position of this step; packed T-1
@@ -1277,7 +586,7 @@ struct KeepShadow16 {
 // Piece PID of a slab step: round PID / 12 handles words J = 2*round + {0, 1}; stage (PID % 12) >> 1 of
 //   x = x0 + pair*kGold; x ^= x>>16 | x *= M1 | x += rk.b; x ^= x>>15 | x *= M2 | x ^= x>>16; saturating x - (T-1) | flags
 template <int WPS, int PID>
-__device__ __forceinline__ void keep_piece16(KeepShadow16& k) {
+__device__ __forceinline__ void keep_piece(KeepShadow& k) {
     constexpr int RND = PID / 12, Q = PID % 12, ST = Q >> 1, R = Q & 1, J = 2 * RND + R;
     constexpr uint32_t CJ = (uint32_t)((J >> 1) * 8 + (J & 1)) * kGold;      // pairs 0, 1, 8, 9 past the step's first
     if constexpr (ST == 0 && J == 0) {
@@ -1310,28 +619,28 @@ __device__ __forceinline__ void keep_piece16(KeepShadow16& k) {
 }
 
 // pieces ride on slots 2 .. 6*WPS+1 of sub-step 1 (before the hand-over; slot 1 carries a fragment read)
-template <int MB, int SUB, int S> __device__ __forceinline__ void shadow_slot16(KeepShadow16& k) {
+template <int MB, int SUB, int S> __device__ __forceinline__ void shadow_slot(KeepShadow& k) {
     constexpr int WPS = MB == 4 ? 4 : 2;
-    if constexpr (SUB == 1 && S >= 2 && S < 2 + 6 * WPS) keep_piece16<WPS, S - 2>(k);
+    if constexpr (SUB == 1 && S >= 2 && S < 2 + 6 * WPS) keep_piece<WPS, S - 2>(k);
 }
 // the same pieces outside any slab step (tiles with fewer than 32 slab steps)
 template <int WPS, int PID = 0>
-__device__ __forceinline__ void keep_pieces_plain16(KeepShadow16& k) {
+__device__ __forceinline__ void keep_pieces_plain(KeepShadow& k) {
     if constexpr (PID < 6 * WPS) {
-        keep_piece16<WPS, PID>(k);
-        keep_pieces_plain16<WPS, PID + 1>(k);
+        keep_piece<WPS, PID>(k);
+        keep_pieces_plain<WPS, PID + 1>(k);
     }
 }
 
-// Column-operand slab lanes for the 16x16x32 layout (see col_slab16_swz): 64 contraction rows x 256 output
-// columns, each row 32 chunks (512 B).  Wave w, pass i fills rows 2*(NWAVES*i + w), +1.
-__device__ __forceinline__ SlabLanes col_slab16_lanes(int64_t ld, int rows_valid, int cols_valid) {
+// Column-operand slab for (5): 64 contraction rows x 256 output columns, each row 32 chunks (512 B).
+// Wave w, pass i fills rows 2*(NWAVES*i + w), +1; lane l is (row l >> 5, physical chunk l & 31).
+__device__ __forceinline__ SlabLanes col_slab_lanes(int64_t ld, int rows_valid, int cols_valid) {
     const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
     SlabLanes s;
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
         const int row = 2 * (NWAVES * i + w) + (l >> 5);
-        const int chunk = min((l & 31) ^ col_slab16_swz(row), (cols_valid >> 3) - 1);
+        const int chunk = min((l & 31) ^ col_slab_swz(row), (cols_valid >> 3) - 1);
         s.off[i] = (uint32_t)((min(row, rows_valid - 1) * ld + chunk * 8) * 2);
     }
     return s;
@@ -1369,9 +678,9 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     const lora_bf16* dYt = p.dY + (int64_t)rt.row_start * p.N;
     const lora_bf16* Wt = p.W + j0;
     const uint32_t lds0 = lds_addr_of(smem);
-    const FragLanes16 fl = frag_lanes16<true>(wn);
+    const FragLanes fl = frag_lanes<true>(wn);
     const int tok_org = wm * (32 * MB) * 128, out_org = TILE_BYTES;      // (the wave's columns are in fl.col_off)
-    const SlabLanes sd = row_slab_lanes(p.N, rt.rows, 8), sw = col_slab16_lanes(p.K, BK, cols_valid);
+    const SlabLanes sd = row_slab_lanes(p.N, rt.rows, 8), sw = col_slab_lanes(p.K, BK, cols_valid);
     const int nk = p.N / BK;
     const int rr = LORA ? p.r : 16;
     const lora_bf16* dSt = p.dS + (int64_t)rt.row_start * rr;
@@ -1381,14 +690,14 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
         load_slab<2 * MB>(lds0, dYt + 0, sd);
         load_slab(lds0 + TILE_BYTES, Wt, sw);
     } else if (LORA) {
-        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sa = col_slab16_lanes(p.K, rr, cols_valid);
+        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sa = col_slab_lanes(p.K, rr, cols_valid);
         load_slab<2 * MB>(lds0, dSt, ss);
         load_slab(lds0 + TILE_BYTES, At, sa);
     }
-    zero_acc16<MB>(acc);                               // while the first slabs are on their way
+    zero_acc<MB>(acc);                               // while the first slabs are on their way
 
     // keep flags: state of the hash pieces, and what changes with the 16-row block row they work on
-    KeepShadow16 ks;
+    KeepShadow ks;
     NoShadow none;
     uint32_t keep_all = 0;
     uint32_t* flags = (uint32_t*)(smem + GEMM_LDS_BYTES) + threadIdx.x;     // [2 * MB][NTHREADS]
@@ -1424,8 +733,8 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
 
     wait_slab_loads();
     __syncthreads();
-    Frags16<MB> f;
-    if (nk > 0) read_frags16<true, MB>(f, smem + tok_org, smem + out_org, fl);
+    Frags<MB> f;
+    if (nk > 0) read_frags<true, MB>(f, smem + tok_org, smem + out_org, fl);
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
     // slab steps 0 .. nk-2 bring the next base slab pair; the first 32 of all steps also carry the hash pieces
     Pipe pp{(const char*)(dYt + BK), (const char*)(Wt + (int64_t)BK * p.K), BK * 2, (int64_t)BK * p.K * 2, 0u};
@@ -1433,16 +742,16 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     if constexpr (LORA) {
         for (; kt < min(nk - 1, FLAG_STEPS); ++kt) {
             keep_step_begin(kt);
-            slab_step16<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sd, sw, true, true, ks);
+            slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sd, sw, true, true, ks);
             keep_step_end(kt);
         }
     }
     for (; kt < nk - 1; ++kt)
-        slab_step16<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sd, sw, true, true, none);
+        slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sd, sw, true, true, none);
     if (nk > 0) {
         // the last base slab: the LoRA slab pair [dS | A] rides in as one more slab (nothing if there is no
         // LoRA term); its lane offsets are formed only now, the main loop has no registers for them
-        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sa = col_slab16_lanes(p.K, rr, cols_valid);
+        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sa = col_slab_lanes(p.K, rr, cols_valid);
         pp.src_tok = (const char*)dSt;
         pp.src_out = (const char*)At;
         if constexpr (LORA) {
@@ -1450,10 +759,10 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
             // past the 32nd step the hash pieces still run, on a step number that is never flushed
             const bool forming = kt < FLAG_STEPS;
             if (forming) keep_step_begin(kt);
-            slab_step16<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sa, true, false, ks);
+            slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sa, true, false, ks);
             if (forming) keep_step_end(kt);
         } else {
-            slab_step16<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sa, false, false, none);
+            slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sa, false, false, none);
         }
     }
     if constexpr (LORA) {
@@ -1461,7 +770,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
 #pragma unroll 1
         for (int kt = min(nk, FLAG_STEPS); kt < FLAG_STEPS; ++kt) {
             keep_step_begin(kt);
-            keep_pieces_plain16<WPS>(ks);
+            keep_pieces_plain<WPS>(ks);
             keep_step_end(kt);
         }
     }
@@ -1481,7 +790,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
 #pragma unroll
         for (int bp = 0; bp < MB; ++bp) {
             const int blk = wm * (32 * MB) + bp * 32;
-            block_store16<MB, false>(acc, bp, nullptr, nullptr, fl, 0, 0u, 0u, stage, out, p.K, blk, rt.rows - blk, col_ok, le);
+            block_store<MB, false>(acc, bp, nullptr, nullptr, fl, 0, 0u, 0u, stage, out, p.K, blk, rt.rows - blk, col_ok, le);
         }
     } else {
         // One run of 64-row groups per adapter present in the tile (a single run unless the tile is mixed).
@@ -1492,7 +801,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
             while (qe < nq && group_adapter(gm, qe) == g) ++qe;
             if (q > 0) {                               // next adapter of a mixed tile: bring its A slab
                 __syncthreads();
-                const SlabLanes sa = col_slab16_lanes(p.K, rr, cols_valid);
+                const SlabLanes sa = col_slab_lanes(p.K, rr, cols_valid);
                 load_slab(lds0 + lo + TILE_BYTES, p.A + (int64_t)g * rr * p.K + j0, sa);
                 wait_slab_loads();
                 __syncthreads();
@@ -1502,7 +811,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
             for (int bp = 0; bp < MB; ++bp) {
                 const int blk = wm * (32 * MB) + bp * 32;          // first tile row of the pair
                 if (blk < 64 * q || blk >= 64 * qe) continue;
-                block_store16<MB, true>(acc, bp, lds_tok, lds_out, fl, rank_chunks, flags_e[(2 * bp) * NTHREADS],
+                block_store<MB, true>(acc, bp, lds_tok, lds_out, fl, rank_chunks, flags_e[(2 * bp) * NTHREADS],
                                         flags_e[(2 * bp + 1) * NTHREADS], stage, out, p.K, blk, rt.rows - blk, col_ok, le);
             }
             q = qe;
