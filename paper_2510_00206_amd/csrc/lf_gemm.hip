@@ -58,45 +58,74 @@ __device__ __forceinline__ uint32_t lds_addr_of(const char* p) {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
 }
 
+// The LDS destination of a copy is M0 + the instruction's immediate offset + 16 * lane, and the same
+// immediate also moves the memory address.  A wave's passes of one slab are therefore laid out 1024 bytes
+// apart (pass i of an NP-pass slab at immediate (i - NP/2) * 1024, M0 pointing at the middle), so that M0 is
+// written once per slab instead of once per copy - a copy is then a single instruction, which matters between
+// MFMAs of 16 cycles; the lane offsets are pre-biased by the opposite amount.  kCopyBias keeps those offsets
+// non-negative: every source address handed to a copy is the slab's first element MINUS kCopyBias bytes (an
+// address that is never dereferenced by itself).
+constexpr int kCopyBias = 4096;
+constexpr int pass_imm(int np, int i) { return (i - np / 2) * 1024; }
+
 // M0 is named as clobbered so that the compiler never keeps a value of its own in it across a copy (it
-// defines M0 itself before indirect register indexing, lane selects and its own LDS-DMA builtins).  Clang
-// warns about every reserved register on a clobber list; the clobber is still recorded, hence the pragma.
+// defines M0 itself before indirect register indexing, lane selects and its own LDS-DMA builtins; none of
+// these occur in the kernels below, whose later passes rely on the M0 of pass 0).  Clang warns about every
+// reserved register on a clobber list; the clobber is still recorded, hence the pragma.
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"
-__device__ __forceinline__ void copy16_to_lds(const char* uniform_base, uint32_t lane_byte_off, uint32_t lds_wave_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_wave_addr), "v"(lane_byte_off), "s"(uniform_base) : "memory", "m0");
+template <int IMM, bool SET_M0>
+__device__ __forceinline__ void copy16_to_lds(const char* biased_base, uint32_t lane_byte_off, uint32_t m0_value) {
+    if constexpr (SET_M0)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3"
+                     :: "s"(m0_value), "v"(lane_byte_off), "s"(biased_base), "n"(IMM) : "memory", "m0");
+    else
+        asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2"
+                     :: "v"(lane_byte_off), "s"(biased_base), "n"(IMM) : "memory");
 }
 #pragma clang diagnostic pop
+
+// M0 of a wave for an NP-pass slab whose first byte is at LDS address `lds_slab_addr`
+template <int NP>
+__device__ __forceinline__ uint32_t slab_m0(uint32_t lds_slab_addr) {
+    const uint32_t w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    return lds_slab_addr + w * (NP * 1024) + (NP / 2) * 1024;
+}
 
 __device__ __forceinline__ void wait_slab_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Per-lane source offsets of one slab (bytes from the slab's first element), one per pass.
 struct SlabLanes { uint32_t off[PASSES]; };
 
-// Row-operand slab: 256 rows (128 for the token slab of a 128-row tile) x 64 contraction elements, each row 8
-// chunks of 16 B (128 B).
-// Wave w, pass i fills rows 8*(NWAVES*i + w) .. +7; lane l is (row l >> 3, physical chunk l & 7).
+// Row-operand slab: 256 rows (NP = 8 passes; 128 rows and NP = 4 for the token slab of a 128-row tile) x 64
+// contraction elements, each row 8 chunks of 16 B (128 B).
+// Wave w, pass i fills rows 8*(NP*w + i) .. +7; lane l is (row l >> 3, physical chunk l & 7).
+template <int NP = PASSES>
 __device__ __forceinline__ SlabLanes row_slab_lanes(int64_t ld, int rows_valid, int nchunk_valid) {
     const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
     SlabLanes s;
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
-        const int row = 8 * (NWAVES * i + w) + (l >> 3);
+        const int ii = i < NP ? i : 0;                 // (passes past NP are never issued)
+        const int row = 8 * (NP * w + ii) + (l >> 3);
         const int chunk = min((l & 7) ^ row_slab_swz(row), nchunk_valid - 1);
-        s.off[i] = (uint32_t)((min(row, rows_valid - 1) * ld + chunk * 8) * 2);
+        s.off[i] = (uint32_t)((min(row, rows_valid - 1) * ld + chunk * 8) * 2 + kCopyBias - pass_imm(NP, ii));
     }
     return s;
 }
 
-// Enqueue one slab (its first NP wave-passes: a 128-row token slab has 4): `src` is the
-// (workgroup-uniform) address of the slab's first element.
+// Enqueue one slab of NP wave-passes (a 128-row token slab has 4): `src` is the (workgroup-uniform) address
+// of the slab's first element, `s` lanes formed for the same NP.
+template <int NP, int I = 0>
+__device__ __forceinline__ void load_slab_passes(const char* biased, const SlabLanes& s, uint32_t m0) {
+    if constexpr (I < NP) {
+        copy16_to_lds<pass_imm(NP, I), I == 0>(biased, s.off[I], m0);
+        load_slab_passes<NP, I + 1>(biased, s, m0);
+    }
+}
 template <int NP = PASSES>
 __device__ __forceinline__ void load_slab(uint32_t lds_slab_addr, const lora_bf16* src, const SlabLanes& s) {
-    const uint32_t wave = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
-#pragma unroll
-    for (int i = 0; i < NP; ++i)
-        copy16_to_lds((const char*)src, s.off[i], lds_slab_addr + i * (NWAVES * 1024) + wave);
+    load_slab_passes<NP>((const char*)src - kCopyBias, s, slab_m0<NP>(lds_slab_addr));
 }
 
 // ---- MFMAs issued from assembly ------------------------------------------------------------------
@@ -111,9 +140,9 @@ struct NoShadow {};        // a slab step without hash pieces
 
 // What the next slab pair is copied from: a token slab of 2*MB wave-passes and an out slab of PASSES.
 struct NextSlabs {
-    const char* src_tok; const char* src_out;     // workgroup-uniform addresses of the slabs' first elements
+    const char* src_tok; const char* src_out;     // workgroup-uniform addresses of the slabs' first elements - kCopyBias
     const SlabLanes& lanes_tok; const SlabLanes& lanes_out;
-    uint32_t lds_tok, lds_out;                    // LDS addresses of the destination slabs (+ this wave's 1024 B)
+    uint32_t m0_tok, m0_out;                      // this wave's M0 values for the destination slabs (slab_m0)
     bool valid;
 };
 
@@ -121,18 +150,25 @@ struct NextSlabs {
 // instructions that ride on MFMA slots, instead of being derived again from the step number at the top of
 // every step (some thirty scalar instructions between two steps, with the matrix pipe idle meanwhile).
 struct Pipe {
-    const char* src_tok; const char* src_out;     // global addresses of the NEXT slab pair's first elements
+    const char* src_tok; const char* src_out;     // global addresses of the NEXT slab pair's first elements - kCopyBias
     int64_t adv_tok, adv_out;                     // their advance per slab step, bytes
     uint32_t rd;                                  // LDS byte offset of the stage being computed on: 0 or STAGE_BYTES
 };
+
+// This wave's M0 values (slab_m0) for the token and the out slab of LDS stage 0.
+struct CopyOrg { uint32_t tok, out; };
+template <int MB>
+__device__ __forceinline__ CopyOrg copy_org(uint32_t lds0) {
+    return CopyOrg{slab_m0<2 * MB>(lds0), slab_m0<PASSES>(lds0 + TILE_BYTES)};
+}
 
 // Copy number J (0 .. 2*MB+PASSES-1) of the next slab pair.
 template <int MB, int J>
 __device__ __forceinline__ void issue_copy(const NextSlabs& nx) {
     if (!nx.valid) return;
     constexpr int TOKP = 2 * MB;
-    if (J < TOKP) copy16_to_lds(nx.src_tok, nx.lanes_tok.off[J], nx.lds_tok + J * (NWAVES * 1024));
-    else copy16_to_lds(nx.src_out, nx.lanes_out.off[J - TOKP], nx.lds_out + (J - TOKP) * (NWAVES * 1024));
+    if constexpr (J < TOKP) copy16_to_lds<pass_imm(TOKP, J), J == 0>(nx.src_tok, nx.lanes_tok.off[J], nx.m0_tok);
+    else copy16_to_lds<pass_imm(PASSES, J - TOKP), J == TOKP>(nx.src_out, nx.lanes_out.off[J - TOKP], nx.m0_out);
 }
 
 // gm.g[q] for a run-time q, as a scalar (wave-uniform) value
@@ -299,12 +335,12 @@ __device__ __forceinline__ void slots(f32x4 (&acc)[2 * MB][8], Frags<MB>& f, con
 // reads of the next slab (if read_next).  On entry f holds the fragments of sub-step 0 of the current slab.
 template <bool COL_SLAB, int MB, class SH>
 __device__ __forceinline__ void slab_step(f32x4 (&acc)[2 * MB][8], Frags<MB>& f, const char* lds_tok_org,
-                                            const char* lds_out_org, uint32_t lds_copy_org, const FragLanes& fl, Pipe& pp,
+                                            const char* lds_out_org, CopyOrg lds_copy_org, const FragLanes& fl, Pipe& pp,
                                             const SlabLanes& lanes_tok, const SlabLanes& lanes_out, bool copy_next,
                                             bool read_next, SH& sh) {
     const uint32_t nxt = STAGE_BYTES - pp.rd;
     const StepLds L{lds_tok_org + pp.rd, lds_out_org + pp.rd, lds_tok_org + nxt, lds_out_org + nxt};
-    const NextSlabs nx{pp.src_tok, pp.src_out, lanes_tok, lanes_out, lds_copy_org + nxt, lds_copy_org + nxt + TILE_BYTES,
+    const NextSlabs nx{pp.src_tok, pp.src_out, lanes_tok, lanes_out, lds_copy_org.tok + nxt, lds_copy_org.out + nxt,
                        copy_next};
     __builtin_amdgcn_sched_barrier(0);
     slots<COL_SLAB, MB, 0>(acc, f, L, fl, nx, read_next, sh, pp);
@@ -439,7 +475,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wm = w & 1, wn = w >> 1;
     const int nk = p.K / BK;
     const uint32_t lds0 = lds_addr_of(smem);
-    const uint32_t wave_lds = w * 1024;
+    const CopyOrg corg = copy_org<MB>(lds0);
     const FragLanes fl = frag_lanes<false>(wn);
     const int tok_org = wm * (32 * MB) * 128, out_org = TILE_BYTES + wn * 128 * 128;
     // p.r == 0 (no LoRA slab) and p.K == 0 (LoRA slab only) serve the unfused baseline's plain GEMMs.
@@ -449,7 +485,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
     Pipe pp{nullptr, nullptr, BK * 2, BK * 2, 0u};
 
     // first slab pair of the first tile
-    SlabLanes sx = row_slab_lanes(p.K, tc.rt.rows, 8), sw = row_slab_lanes(p.K, tc.cols_valid, 8);
+    SlabLanes sx = row_slab_lanes<2 * MB>(p.K, tc.rt.rows, 8), sw = row_slab_lanes(p.K, tc.cols_valid, 8);
     if (nk > 0) {
         load_slab<2 * MB>(lds0, p.X + (int64_t)tc.rt.row_start * p.K, sx);
         load_slab(lds0 + TILE_BYTES, p.W + (int64_t)tc.c0 * p.K, sw);
@@ -463,7 +499,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
         const lora_bf16* Ssrc = p.S + (int64_t)rt.row_start * p.r;
         const lora_bf16* Bsrc = p.B + ((int64_t)rt.g * p.N + n0) * p.r;
         if (nk == 0) {
-            const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
+            const SlabLanes ss = row_slab_lanes<2 * MB>(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
             load_slab<2 * MB>(lds0 + pp.rd, Ssrc, ss);
             load_slab(lds0 + pp.rd + TILE_BYTES, Bsrc, sb);
         }
@@ -473,19 +509,19 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
         __syncthreads();
         Frags<MB> f;
         if (nk > 0) read_frags<false, MB>(f, smem + pp.rd + tok_org, smem + pp.rd + out_org, fl);
-        pp.src_tok = (const char*)(Xt + BK);
-        pp.src_out = (const char*)(Wt + BK);
+        pp.src_tok = (const char*)(Xt + BK) - kCopyBias;
+        pp.src_out = (const char*)(Wt + BK) - kCopyBias;
         for (int kt = 0; kt + 1 < nk; ++kt)
-            slab_step<false, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sx, sw, true, true, none);
+            slab_step<false, MB>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, sx, sw, true, true, none);
         // the lane offsets of the LoRA slab pair are formed only now: through the main loop they would cost
         // sixteen registers that it does not have
-        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
+        const SlabLanes ss = row_slab_lanes<2 * MB>(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
         if (nk > 0) {
             // after the last base slab the LoRA step rides as one more slab: token operand S' [rows, r],
             // out operand B [N, r]
-            pp.src_tok = (const char*)Ssrc;
-            pp.src_out = (const char*)Bsrc;
-            slab_step<false, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sb,
+            pp.src_tok = (const char*)Ssrc - kCopyBias;
+            pp.src_out = (const char*)Bsrc - kCopyBias;
+            slab_step<false, MB>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sb,
                                    has_lora && !gm.mixed, false, none);
         }
         const uint32_t lo = pp.rd;                     // the stage that holds (or receives) the LoRA slab pair
@@ -499,7 +535,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
         const bool has_next = next < total;
         if (has_next) {
             tc = decode_tile(p.tb, p.M, BM, p.uniform_tiles, p.tiles_m, p.tiles_n, next, p.N);
-            sx = row_slab_lanes(p.K, tc.rt.rows, 8);
+            sx = row_slab_lanes<2 * MB>(p.K, tc.rt.rows, 8);
             sw = row_slab_lanes(p.K, tc.cols_valid, 8);
             if (nk > 0) {
                 load_slab<2 * MB>(lds0 + (STAGE_BYTES - lo), p.X + (int64_t)tc.rt.row_start * p.K, sx);
@@ -633,15 +669,15 @@ __device__ __forceinline__ void keep_pieces_plain(KeepShadow& k) {
 }
 
 // Column-operand slab for (5): 64 contraction rows x 256 output columns, each row 32 chunks (512 B).
-// Wave w, pass i fills rows 2*(NWAVES*i + w), +1; lane l is (row l >> 5, physical chunk l & 31).
+// Wave w, pass i fills rows 2*(PASSES*w + i), +1; lane l is (row l >> 5, physical chunk l & 31).
 __device__ __forceinline__ SlabLanes col_slab_lanes(int64_t ld, int rows_valid, int cols_valid) {
     const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
     SlabLanes s;
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
-        const int row = 2 * (NWAVES * i + w) + (l >> 5);
+        const int row = 2 * (PASSES * w + i) + (l >> 5);
         const int chunk = min((l & 31) ^ col_slab_swz(row), (cols_valid >> 3) - 1);
-        s.off[i] = (uint32_t)((min(row, rows_valid - 1) * ld + chunk * 8) * 2);
+        s.off[i] = (uint32_t)((min(row, rows_valid - 1) * ld + chunk * 8) * 2 + kCopyBias - pass_imm(PASSES, i));
     }
     return s;
 }
@@ -680,7 +716,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     const uint32_t lds0 = lds_addr_of(smem);
     const FragLanes fl = frag_lanes<true>(wn);
     const int tok_org = wm * (32 * MB) * 128, out_org = TILE_BYTES;      // (the wave's columns are in fl.col_off)
-    const SlabLanes sd = row_slab_lanes(p.N, rt.rows, 8), sw = col_slab_lanes(p.K, BK, cols_valid);
+    const SlabLanes sd = row_slab_lanes<2 * MB>(p.N, rt.rows, 8), sw = col_slab_lanes(p.K, BK, cols_valid);
     const int nk = p.N / BK;
     const int rr = LORA ? p.r : 16;
     const lora_bf16* dSt = p.dS + (int64_t)rt.row_start * rr;
@@ -690,7 +726,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
         load_slab<2 * MB>(lds0, dYt + 0, sd);
         load_slab(lds0 + TILE_BYTES, Wt, sw);
     } else if (LORA) {
-        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sa = col_slab_lanes(p.K, rr, cols_valid);
+        const SlabLanes ss = row_slab_lanes<2 * MB>(rr, rt.rows, rr >> 3), sa = col_slab_lanes(p.K, rr, cols_valid);
         load_slab<2 * MB>(lds0, dSt, ss);
         load_slab(lds0 + TILE_BYTES, At, sa);
     }
@@ -735,34 +771,34 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     __syncthreads();
     Frags<MB> f;
     if (nk > 0) read_frags<true, MB>(f, smem + tok_org, smem + out_org, fl);
-    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) * 1024);
+    const CopyOrg corg = copy_org<MB>(lds0);
     // slab steps 0 .. nk-2 bring the next base slab pair; the first 32 of all steps also carry the hash pieces
-    Pipe pp{(const char*)(dYt + BK), (const char*)(Wt + (int64_t)BK * p.K), BK * 2, (int64_t)BK * p.K * 2, 0u};
+    Pipe pp{(const char*)(dYt + BK) - kCopyBias, (const char*)(Wt + (int64_t)BK * p.K) - kCopyBias, BK * 2, (int64_t)BK * p.K * 2, 0u};
     int kt = 0;
     if constexpr (LORA) {
         for (; kt < min(nk - 1, FLAG_STEPS); ++kt) {
             keep_step_begin(kt);
-            slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sd, sw, true, true, ks);
+            slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, sd, sw, true, true, ks);
             keep_step_end(kt);
         }
     }
     for (; kt < nk - 1; ++kt)
-        slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, sd, sw, true, true, none);
+        slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, sd, sw, true, true, none);
     if (nk > 0) {
         // the last base slab: the LoRA slab pair [dS | A] rides in as one more slab (nothing if there is no
         // LoRA term); its lane offsets are formed only now, the main loop has no registers for them
-        const SlabLanes ss = row_slab_lanes(rr, rt.rows, rr >> 3), sa = col_slab_lanes(p.K, rr, cols_valid);
-        pp.src_tok = (const char*)dSt;
-        pp.src_out = (const char*)At;
+        const SlabLanes ss = row_slab_lanes<2 * MB>(rr, rt.rows, rr >> 3), sa = col_slab_lanes(p.K, rr, cols_valid);
+        pp.src_tok = (const char*)dSt - kCopyBias;
+        pp.src_out = (const char*)At - kCopyBias;
         if constexpr (LORA) {
             // one code path for this step whatever kt is (two would have to merge all the accumulators):
             // past the 32nd step the hash pieces still run, on a step number that is never flushed
             const bool forming = kt < FLAG_STEPS;
             if (forming) keep_step_begin(kt);
-            slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sa, true, false, ks);
+            slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sa, true, false, ks);
             if (forming) keep_step_end(kt);
         } else {
-            slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, lds0 + wave_lds, fl, pp, ss, sa, false, false, none);
+            slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sa, false, false, none);
         }
     }
     if constexpr (LORA) {
