@@ -246,6 +246,19 @@ __device__ __forceinline__ bf16x8 read_out_frag(const char* lds_out, const FragL
         return __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_out + fl.row_off[sub] + blk * 2048));
     }
 }
+// One half of a column-slab out fragment (contraction rows +0..3 or +4..7 of the lane's eight): in a 256-row
+// tile the two transposing reads of a fragment ride on two MFMA slots (together with their address they do not
+// fit between two MFMAs of 16 cycles).
+template <int HALF>
+__device__ __forceinline__ void read_out_frag_half(bf16x8& dst, const char* lds_out, const FragLanes& fl, int blk, int sub) {
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    const s16x4 h = lds_read_tr(lds_out, (fl.col_off ^ (blk << 5)) + sub * 16384 + HALF * 2048);
+    const s16x8 hw = __builtin_shufflevector(h, h, 0, 1, 2, 3, 0, 1, 2, 3);
+    const s16x8 x = __builtin_bit_cast(s16x8, dst);
+    const s16x8 y = HALF ? __builtin_shufflevector(x, hw, 0, 1, 2, 3, 8, 9, 10, 11)
+                         : __builtin_shufflevector(hw, x, 0, 1, 2, 3, 12, 13, 14, 15);
+    dst = __builtin_bit_cast(bf16x8, y);
+}
 __device__ __forceinline__ bf16x8 read_tok_frag(const char* lds_tok, const FragLanes& fl, int blk, int sub) {
     return __builtin_bit_cast(bf16x8, *(const u32x4*)(lds_tok + fl.row_off[sub] + blk * 2048));
 }
@@ -268,6 +281,11 @@ template <int MB> struct Sched {
         if (sub == 0) return MB == 4 ? ((s & 7) == 4 ? s >> 3 : -1) : ((s & 3) == 0 ? s >> 2 : -1);
         const int d = s - (HO + 1);
         return d >= 0 && d < 16 && (d & 1) == 0 ? d >> 1 : -1;
+    }
+    // column slab, 256-row tile: the second transposing read of out fragment k (the first rides on fo_read's slot)
+    static constexpr int fo_read_hi(int sub, int s) {
+        if (sub == 0) return (s & 7) == 5 ? s >> 3 : -1;
+        return s >= 53 && s <= 55 ? s - 53 : s >= 57 && s <= 61 ? s - 54 : -1;      // 53,54,55,57..61 -> 0 .. 7
     }
     // reload of token fragment mi; slot 1 brings the last block's fragment of THIS sub-step (its row is not
     // over when the others are reloaded), the others that of the next sub-step
@@ -303,10 +321,20 @@ __device__ __forceinline__ void slots(f32x4 (&acc)[2 * MB][8], Frags<MB>& f, con
     using SC = Sched<MB>;
     constexpr int sub = S / SC::SS, s = S % SC::SS, mi = s >> 3, ni = s & 7;
     acc[mi][ni] = LF_MFMA(f.fo[sub][ni], f.ft[mi], acc[mi][ni]);
+    constexpr bool SPLIT = COL_SLAB && MB == 4;      // the two halves of an out fragment on two slots
     constexpr int k = SC::fo_read(sub, s);
-    if constexpr (k >= 0) {
+    if constexpr (k >= 0 && !SPLIT) {
         if constexpr (sub == 0) f.fo[1][k] = read_out_frag<COL_SLAB>(L.cur_out, fl, k, 1);
         else if (read_next) f.fo[0][k] = read_out_frag<COL_SLAB>(L.nxt_out, fl, k, 0);
+    }
+    if constexpr (k >= 0 && SPLIT) {
+        if constexpr (sub == 0) read_out_frag_half<0>(f.fo[1][k], L.cur_out, fl, k, 1);
+        else if (read_next) read_out_frag_half<0>(f.fo[0][k], L.nxt_out, fl, k, 0);
+    }
+    constexpr int kh = SPLIT ? SC::fo_read_hi(sub, s) : -1;
+    if constexpr (kh >= 0) {
+        if constexpr (sub == 0) read_out_frag_half<1>(f.fo[1][kh], L.cur_out, fl, kh, 1);
+        else if (read_next) read_out_frag_half<1>(f.fo[0][kh], L.nxt_out, fl, kh, 0);
     }
     constexpr int m = SC::ft_read(sub, s);
     if constexpr (m >= 0) {
