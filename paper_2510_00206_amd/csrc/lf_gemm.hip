@@ -299,10 +299,18 @@ template <int MB> struct Sched {
         return s == 16 ? 0 : s == 18 ? 1 : s == 24 ? 2 : -1;
     }
     // copy number (0 .. 2*MB + 7) of the next slab pair
-    static constexpr int copy_at(int sub, int s) {
+    // `early` (operation (2)): as early as the reads allow - the last copies then have the longest to land, which
+    // counts when the operands come from HBM; operation (5), whose slots also carry the transposing reads, is
+    // faster with the copies spread over the whole sub-step
+    static constexpr int copy_at(int sub, int s, bool early) {
         if (sub != 0) return -1;
-        if (MB == 4) return (s & 3) == 2 ? s >> 2 : -1;                           // 2, 6, .. 62 -> 0 .. 15
-        return (s & 1) && s >= 3 && s <= 25 ? (s - 3) >> 1 : -1;                  // 3, 5, .. 25 -> 0 .. 11
+        if (MB == 4 && !early) return (s & 3) == 2 ? s >> 2 : -1;                               // 2, 6, .. 62 -> 0 .. 15
+        if (MB == 4) return s < 32 && (s & 2) ? (s >> 3) * 4 + (s & 1) + ((s & 4) >> 1) : -1;   // 2,3,6,7, 10,11,.. -> 0 .. 15
+        // 128-row tile: slots 2 .. 19 that carry no read
+        constexpr int at[12] = {2, 3, 5, 6, 7, 9, 11, 13, 14, 15, 17, 19};
+        for (int j = 0; j < 12; ++j)
+            if (at[j] == s) return j;
+        return -1;
     }
 };
 
@@ -342,7 +350,7 @@ __device__ __forceinline__ void slots(f32x4 (&acc)[2 * MB][8], Frags<MB>& f, con
         else if constexpr (sub == 0) f.ft[m] = read_tok_frag(L.cur_tok, fl, m, 1);
         else if (read_next) f.ft[m] = read_tok_frag(L.nxt_tok, fl, m, 0);
     }
-    constexpr int j = SC::copy_at(sub, s);
+    constexpr int j = SC::copy_at(sub, s, !COL_SLAB);
     if constexpr (j >= 0) issue_copy<MB, j>(nx);
     shadow_slot<MB, sub, s>(sh);
     if constexpr (sub == 1 && s == 0) {
