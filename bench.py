@@ -40,8 +40,8 @@ def read_traffic(workload: str):
 
 def measure_ceilings(torch, binding, dev, operands):
     """What this GPU sustains with nothing in the way (library diagnostics, timed with events on the launch
-    stream): the GEMM kernels' MFMA instruction in a register-resident loop on `operands` (values of the
-    workload's distribution), one plain read of a 2 GiB buffer (eight times the memory-side cache), and
+    stream): the GEMM kernels' MFMA instruction (and the other bf16 MFMA shape) in a register-resident loop on
+    `operands` (values of the workload's distribution), one plain read of a 2 GiB buffer (eight times the memory-side cache), and
     plain reads the size of `operands` (what one streaming kernel of the path reads), one launch each,
     every launch on a window of the big buffer that no earlier launch of the series has touched."""
     def timed(fn, reps, skip):
@@ -75,18 +75,21 @@ def measure_ceilings(torch, binding, dev, operands):
     ms_win = timed(read_window, nwin, nwin // 4) if nwin >= 4 else None
     del big
 
-    # the matrix loop last: the timed steps then start from the chip's state under its heaviest load
+    # the matrix loops last: the timed steps then start from the chip's state under its heaviest load
     wgs, iters = 2048, 1536
     sink = torch.empty(wgs * 256, dtype=torch.float32, device=dev)
     flops = [0.0]
-
-    def mfma():
-        flops[0] = binding.ceiling_mfma(operands, sink, wgs, iters)
-    ms = timed(mfma, 8, 3)                      # about 60 ms in all: the sustained rate, not the first burst
-    mfma_tflops = flops[0] / (ms * 1e-3) / 1e12
-    out = {"mfma_bf16_tflops": round(mfma_tflops, 1), "hbm_read_gbs": round(read_gbs, 1),
-           "how": "register-resident v_mfma_f32_32x32x16_bf16 loop, 16 chains per wave, 1 wave per SIMD, operands = "
-                  "the workload's X values; plain 16-byte-per-lane read of 2 GiB; the same read in single launches "
+    rates = {}
+    for shape in (32, 16):                      # the GEMM kernels' own instruction (16x16x32) last
+        def mfma():
+            flops[0] = binding.ceiling_mfma(operands, sink, wgs, iters, shape)
+        ms = timed(mfma, 8, 3)                  # about 55 ms in all: the sustained rate, not the first burst
+        rates[shape] = flops[0] / (ms * 1e-3) / 1e12
+    out = {"mfma_bf16_tflops": round(rates[16], 1), "mfma_bf16_tflops_32x32x16": round(rates[32], 1),
+           "hbm_read_gbs": round(read_gbs, 1),
+           "how": "register-resident MFMA loops, 256 accumulators per lane in independent chains, 1 wave per SIMD, operands = "
+                  "the workload's X values: v_mfma_f32_16x16x32_bf16 (the GEMM kernels' instruction) and, for comparison, "
+                  "v_mfma_f32_32x32x16_bf16; plain 16-byte-per-lane read of 2 GiB; the same read in single launches "
                   "of sizeof(X) bytes on untouched windows"}
     if ms_win:
         out["hbm_read_one_launch_gbs"] = round(win / (ms_win * 1e-3) / 1e9, 1)

@@ -212,17 +212,19 @@ lora_status lora_frozen_bwd(const lora_bf16* dY, const lora_bf16* W, int64_t M, 
 
 /* Measured ceilings (diagnostics for benchmarks): what the GPU sustains in the two regimes that bound the
  * fused operations of Section 5.1, to set beside its published peaks.
- * lora_ceiling_mfma: `workgroups` workgroups of four waves (one per SIMD) each run `iters` rounds of 32
- *   v_mfma_f32_32x32x16_bf16 on 16 independent accumulator chains - the instruction and register blocking
- *   of operations (2) and (5) - with operands read once from `operands` (device, at least 64 KiB of bf16
- *   values of the caller's choice: the sustained rate depends on the data) and no memory traffic in the
- *   loop.  sink: device, workgroups * 256 floats, overwritten.  *flops (host, may be NULL) receives the
- *   floating-point operations of the launch; the caller times it.
+ * lora_ceiling_mfma: `workgroups` workgroups of four waves (one per SIMD) each run `iters` rounds of 2^20
+ *   floating-point operations per wave: shape 16 = 64 v_mfma_f32_16x16x32_bf16 on 64 independent accumulator
+ *   chains - the instruction and register blocking of operations (2) and (5) - shape 32 = 32
+ *   v_mfma_f32_32x32x16_bf16 on 16 chains (the other bf16 MFMA shape, for comparison); operands are read once
+ *   from `operands` (device, at least 64 KiB of bf16 values of the caller's choice: the sustained rate
+ *   depends on the data) and there is no memory traffic in the loop.  sink: device, workgroups * 256 floats,
+ *   overwritten.  *flops (host, may be NULL) receives the floating-point operations of the launch; the
+ *   caller times it.  Any other shape: LORA_ERR_PARAM.
  * lora_ceiling_hbm_read: `workgroups` workgroups of 256 lanes read `bytes` bytes (a multiple of 16) from
  *   src once, 16 bytes per lane and load, and do nothing else.  sink: device, workgroups * 256 words.
  * Only enqueue on `stream`; allocate nothing.  Bad counts: LORA_ERR_PARAM. */
 lora_status lora_ceiling_mfma(const lora_bf16* operands, float* sink, int32_t workgroups, int32_t iters,
-                              double* flops, lora_stream stream);
+                              int32_t shape, double* flops, lora_stream stream);
 lora_status lora_ceiling_hbm_read(const void* src, size_t bytes, uint32_t* sink, int32_t workgroups,
                                   lora_stream stream);
 

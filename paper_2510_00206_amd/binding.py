@@ -64,7 +64,7 @@ def load_library() -> C.CDLL:
     lib.lora_unfused_fwd.restype = C.c_int
     lib.lora_unfused_bwd.restype = C.c_int
     lib.lora_profile_end.argtypes = [C.POINTER(F), C.POINTER(I32)]
-    lib.lora_ceiling_mfma.argtypes = [P, P, I32, I32, C.POINTER(C.c_double), P]
+    lib.lora_ceiling_mfma.argtypes = [P, P, I32, I32, I32, C.POINTER(C.c_double), P]
     lib.lora_ceiling_mfma.restype = C.c_int
     lib.lora_ceiling_hbm_read.argtypes = [P, SZ, P, I32, P]
     lib.lora_ceiling_hbm_read.restype = C.c_int
@@ -269,11 +269,12 @@ def frozen_bwd(dY, W, dX=None):
     return dX
 
 
-def ceiling_mfma(operands, sink, workgroups, iters) -> float:
-    """Enqueues the register-resident MFMA loop; returns the floating-point operations of the launch."""
+def ceiling_mfma(operands, sink, workgroups, iters, shape=16) -> float:
+    """Enqueues the register-resident MFMA loop (shape 16: the GEMM kernels' 16x16x32 instruction, 32: 32x32x16);
+    returns the floating-point operations of the launch."""
     assert operands.numel() * operands.element_size() >= 65536 and sink.numel() >= workgroups * 256
     flops = C.c_double()
-    _check(load_library().lora_ceiling_mfma(_ptr(operands), _ptr(sink), workgroups, iters, C.byref(flops), _stream()))
+    _check(load_library().lora_ceiling_mfma(_ptr(operands), _ptr(sink), workgroups, iters, shape, C.byref(flops), _stream()))
     return flops.value
 
 

@@ -141,11 +141,12 @@ def test_ceiling_diagnostics_validate_on_the_host(lib):
     ok_ptr = C.c_void_p(0x1000)
     flops = C.c_double(0.0)
     m = lib.lora_ceiling_mfma
-    assert m(None, ok_ptr, 256, 16, C.byref(flops), None) == 1
-    assert m(ok_ptr, None, 256, 16, C.byref(flops), None) == 1
-    assert m(ok_ptr, ok_ptr, 0, 16, C.byref(flops), None) == 4
-    assert m(ok_ptr, ok_ptr, 256, 0, C.byref(flops), None) == 4
-    assert m(C.c_void_p(0x1008), ok_ptr, 256, 16, C.byref(flops), None) == 3
+    assert m(None, ok_ptr, 256, 16, 16, C.byref(flops), None) == 1
+    assert m(ok_ptr, None, 256, 16, 32, C.byref(flops), None) == 1
+    assert m(ok_ptr, ok_ptr, 0, 16, 16, C.byref(flops), None) == 4
+    assert m(ok_ptr, ok_ptr, 256, 0, 16, C.byref(flops), None) == 4
+    assert m(ok_ptr, ok_ptr, 256, 16, 8, C.byref(flops), None) == 4          # neither MFMA shape
+    assert m(C.c_void_p(0x1008), ok_ptr, 256, 16, 16, C.byref(flops), None) == 3
     r = lib.lora_ceiling_hbm_read
     assert r(None, 1 << 20, ok_ptr, 256, None) == 1
     assert r(ok_ptr, 1 << 20, None, 256, None) == 1
