@@ -275,12 +275,12 @@ __device__ __forceinline__ void read_frags(Frags<MB>& f, const char* lds_tok, co
 // What rides on MFMA slot s of sub-step `sub` (s = 8 * token block + out block; -1: nothing).
 template <int MB> struct Sched {
     static constexpr int TB = 2 * MB, SS = 8 * TB;
-    static constexpr int HO = MB == 4 ? 36 : 14;          // sub-step 1: hand-over after this slot
+    static constexpr int HO = MB == 4 ? 36 : 20;          // sub-step 1: hand-over after this slot
     // read of out fragment k for the next sub-step (sub-step 0: of this slab; sub-step 1: of the next slab)
     static constexpr int fo_read(int sub, int s) {
         if (sub == 0) return MB == 4 ? ((s & 7) == 4 ? s >> 3 : -1) : ((s & 3) == 0 ? s >> 2 : -1);
-        const int d = s - (HO + 1);
-        return d >= 0 && d < 16 && (d & 1) == 0 ? d >> 1 : -1;
+        if (MB == 4) return s > HO && s <= HO + 15 && ((s - HO) & 1) ? (s - HO - 1) >> 1 : -1;    // 37, 39, .. 51
+        return s >= HO + 2 && s <= HO + 9 ? s - HO - 2 : -1;                                      // 22 .. 29
     }
     // column slab, 256-row tile: the second transposing read of out fragment k (the first rides on fo_read's slot)
     static constexpr int fo_read_hi(int sub, int s) {
@@ -296,15 +296,18 @@ template <int MB> struct Sched {
             return (s & 7) == 2 && s >= 10 ? (s >> 3) - 1 : -1;                   // 10, 18, 26 -> 0 .. 2
         }
         if (MB == 4) return s >= 38 && s <= 46 && !(s & 1) ? (s - 38) >> 1 : s == 48 ? 5 : s == 56 ? 6 : -1;
-        return s == 16 ? 0 : s == 18 ? 1 : s == 24 ? 2 : -1;
+        return s == 21 ? 0 : s == 30 ? 1 : s == 31 ? 2 : -1;
     }
     // copy number (0 .. 2*MB + 7) of the next slab pair
-    // `early` (operation (2)): as early as the reads allow - the last copies then have the longest to land, which
-    // counts when the operands come from HBM; operation (5), whose slots also carry the transposing reads, is
-    // faster with the copies spread over the whole sub-step
-    static constexpr int copy_at(int sub, int s, bool early) {
+    // mode 1: as early as the reads allow - the last copies then have the longest to land, which counts when the
+    // operands come from HBM; mode 0: spread over the whole sub-step (operation (5), whose slots also carry the
+    // transposing reads, is faster with this); mode 2: as dense as mode 1 but a quarter of a sub-step later (the
+    // even waves of operation (2) when the waves of a workgroup take turns, see fwd_gemm_kernel)
+    static constexpr int copy_at(int sub, int s, int mode) {
         if (sub != 0) return -1;
-        if (MB == 4 && !early) return (s & 3) == 2 ? s >> 2 : -1;                               // 2, 6, .. 62 -> 0 .. 15
+        if (MB == 4 && mode == 0) return (s & 3) == 2 ? s >> 2 : -1;                               // 2, 6, .. 62 -> 0 .. 15
+        if (MB == 4 && mode == 2)                                                                  // 18,19,22,23, .. 46,47
+            return s >= 16 && s < 48 && (s & 2) ? ((s - 16) >> 3) * 4 + (s & 1) + ((s & 4) >> 1) : -1;
         if (MB == 4) return s < 32 && (s & 2) ? (s >> 3) * 4 + (s & 1) + ((s & 4) >> 1) : -1;   // 2,3,6,7, 10,11,.. -> 0 .. 15
         // 128-row tile: slots 2 .. 19 that carry no read
         constexpr int at[12] = {2, 3, 5, 6, 7, 9, 11, 13, 14, 15, 17, 19};
@@ -323,7 +326,7 @@ struct StepLds {
     const char* nxt_tok; const char* nxt_out;     // ... and in the slabs being filled
 };
 
-template <bool COL_SLAB, int MB, int S, class SH>
+template <bool COL_SLAB, int MB, int S, int EARLY, class SH>
 __device__ __forceinline__ void slots(f32x4 (&acc)[2 * MB][8], Frags<MB>& f, const StepLds& L, const FragLanes& fl,
                                         const NextSlabs& nx, bool read_next, SH& sh, Pipe& pp) {
     using SC = Sched<MB>;
@@ -350,7 +353,7 @@ __device__ __forceinline__ void slots(f32x4 (&acc)[2 * MB][8], Frags<MB>& f, con
         else if constexpr (sub == 0) f.ft[m] = read_tok_frag(L.cur_tok, fl, m, 1);
         else if (read_next) f.ft[m] = read_tok_frag(L.nxt_tok, fl, m, 0);
     }
-    constexpr int j = SC::copy_at(sub, s, !COL_SLAB);
+    constexpr int j = SC::copy_at(sub, s, EARLY);
     if constexpr (j >= 0) issue_copy<MB, j>(nx);
     shadow_slot<MB, sub, s>(sh);
     if constexpr (sub == 1 && s == 0) {
@@ -363,13 +366,13 @@ __device__ __forceinline__ void slots(f32x4 (&acc)[2 * MB][8], Frags<MB>& f, con
         wait_slab_loads();
         __syncthreads();
     }
-    if constexpr (S + 1 < 2 * SC::SS) slots<COL_SLAB, MB, S + 1>(acc, f, L, fl, nx, read_next, sh, pp);
+    if constexpr (S + 1 < 2 * SC::SS) slots<COL_SLAB, MB, S + 1, EARLY>(acc, f, L, fl, nx, read_next, sh, pp);
 }
 
 // One 64-deep slab pair: two sub-steps of 16*MB MFMAs; the copies of the next slab pair ride on sub-step 0,
 // the hand-over (copies landed, workgroup barrier) sits in sub-step 1 and is followed by the first fragment
 // reads of the next slab (if read_next).  On entry f holds the fragments of sub-step 0 of the current slab.
-template <bool COL_SLAB, int MB, class SH>
+template <bool COL_SLAB, int MB, int EARLY = 0, class SH>
 __device__ __forceinline__ void slab_step(f32x4 (&acc)[2 * MB][8], Frags<MB>& f, const char* lds_tok_org,
                                             const char* lds_out_org, CopyOrg lds_copy_org, const FragLanes& fl, Pipe& pp,
                                             const SlabLanes& lanes_tok, const SlabLanes& lanes_out, bool copy_next,
@@ -379,7 +382,7 @@ __device__ __forceinline__ void slab_step(f32x4 (&acc)[2 * MB][8], Frags<MB>& f,
     const NextSlabs nx{pp.src_tok, pp.src_out, lanes_tok, lanes_out, lds_copy_org.tok + nxt, lds_copy_org.out + nxt,
                        copy_next};
     __builtin_amdgcn_sched_barrier(0);
-    slots<COL_SLAB, MB, 0>(acc, f, L, fl, nx, read_next, sh, pp);
+    slots<COL_SLAB, MB, 0, EARLY>(acc, f, L, fl, nx, read_next, sh, pp);
     pp.rd = nxt;
 }
 
@@ -499,8 +502,8 @@ __device__ __forceinline__ void block_store(f32x4 (&acc)[2 * MB][8], int bp, con
 
 
 // ---- operation (2): Y = X W + S' B ---------------------------------------------------------------
-template <int MB>
-__global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
+template <int MB, int EARLY>
+__device__ __forceinline__ void fwd_gemm_body(const FwdGemmArgs& p) {
     constexpr int BM = 64 * MB, TB = 2 * MB;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int total = p.tiles_m * p.tiles_n;
@@ -548,7 +551,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
         pp.src_tok = (const char*)(Xt + BK) - kCopyBias;
         pp.src_out = (const char*)(Wt + BK) - kCopyBias;
         for (int kt = 0; kt + 1 < nk; ++kt)
-            slab_step<false, MB>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, sx, sw, true, true, none);
+            slab_step<false, MB, EARLY>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, sx, sw, true, true, none);
         // the lane offsets of the LoRA slab pair are formed only now: through the main loop they would cost
         // sixteen registers that it does not have
         const SlabLanes ss = row_slab_lanes<2 * MB>(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
@@ -557,7 +560,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
             // out operand B [N, r]
             pp.src_tok = (const char*)Ssrc - kCopyBias;
             pp.src_out = (const char*)Bsrc - kCopyBias;
-            slab_step<false, MB>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sb,
+            slab_step<false, MB, EARLY>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sb,
                                    has_lora && !gm.mixed, false, none);
         }
         const uint32_t lo = pp.rd;                     // the stage that holds (or receives) the LoRA slab pair
@@ -639,6 +642,19 @@ __global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
         id = next;
         pp.rd = STAGE_BYTES - lo;
     }
+}
+
+// The four waves of a workgroup run in lockstep (one barrier per slab step), so whatever they do in the same
+// slot they do at the same time; when all four issue their copies together, the hand-over costs 5 % of the
+// kernel as long as the operands come from the caches (taking out either its wait or its barrier gives that
+// back - it is the joint arrival that costs).  STAG: odd waves issue their copies early in the step and even
+// waves in its middle: two instantiations of the whole body that never meet again (a branch that rejoined
+// would have to merge the accumulators); every wave passes the same barriers in either.  With operands that
+// stream from HBM the copies need all the time they can get: then every wave issues them early.
+template <int MB, bool STAG>
+__global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
+    if (!STAG || (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) & 1)) fwd_gemm_body<MB, 1>(p);
+    else fwd_gemm_body<MB, 2>(p);
 }
 
 // ---- dropout keep flags formed in the shadow of the matrix work (operation (5)) ---------------------
@@ -951,9 +967,15 @@ hipError_t launch_fwd_gemm(FwdGemmArgs a, int forced, hipStream_t st) {
     a.uniform_tiles = t.uniform;
     a.tiles_m = t.tiles_m;
     if (a.tiles_m == 0) return hipSuccess;
-    static bool attr_set[2] = {false, false};
-    return t.bm == 256 ? launch_gemm(fwd_gemm_kernel<4>, attr_set[0], a, st, GEMM_LDS_TOTAL, true)
-                       : launch_gemm(fwd_gemm_kernel<2>, attr_set[1], a, st, GEMM_LDS_TOTAL, true);
+    static bool attr_set[4] = {false, false, false, false};
+    // a frozen weight of up to 64 MB stays in the 256 MB memory-side cache beside the activations: the waves
+    // then take turns with their copies (measured: 2 % faster at K = N = 4096, 2 - 5 % slower with 117 and 470 MB)
+    const bool stag = (int64_t)a.K * a.N * 2 <= (64ll << 20);
+    if (t.bm == 256)
+        return stag ? launch_gemm(fwd_gemm_kernel<4, true>, attr_set[0], a, st, GEMM_LDS_TOTAL, true)
+                    : launch_gemm(fwd_gemm_kernel<4, false>, attr_set[1], a, st, GEMM_LDS_TOTAL, true);
+    return stag ? launch_gemm(fwd_gemm_kernel<2, true>, attr_set[2], a, st, GEMM_LDS_TOTAL, true)
+                : launch_gemm(fwd_gemm_kernel<2, false>, attr_set[3], a, st, GEMM_LDS_TOTAL, true);
 }
 
 hipError_t launch_bwd_dx(DxGemmArgs a, int forced, hipStream_t st) {
