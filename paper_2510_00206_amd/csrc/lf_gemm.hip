@@ -279,13 +279,13 @@ template <int MB> struct Sched {
     // read of out fragment k for the next sub-step (sub-step 0: of this slab; sub-step 1: of the next slab)
     static constexpr int fo_read(int sub, int s) {
         if (sub == 0) return MB == 4 ? ((s & 7) == 4 ? s >> 3 : -1) : ((s & 3) == 0 ? s >> 2 : -1);
-        if (MB == 4) return s > HO && s <= HO + 15 && ((s - HO) & 1) ? (s - HO - 1) >> 1 : -1;    // 37, 39, .. 51
+        if (MB == 4) return s == 37 ? 0 : s >= 40 && s <= 52 && !(s & 1) ? (s - 38) >> 1 : -1;      // 37, 40, 42, .. 52 (in the order of their first use)
         return s >= HO + 2 && s <= HO + 9 ? s - HO - 2 : -1;                                      // 22 .. 29
     }
     // column slab, 256-row tile: the second transposing read of out fragment k (the first rides on fo_read's slot)
     static constexpr int fo_read_hi(int sub, int s) {
         if (sub == 0) return (s & 7) == 5 ? s >> 3 : -1;
-        return s >= 53 && s <= 55 ? s - 53 : s >= 57 && s <= 61 ? s - 54 : -1;      // 53,54,55,57..61 -> 0 .. 7
+        return s == 38 ? 0 : s >= 41 && s <= 53 && (s & 1) ? (s - 39) >> 1 : -1;    // right after the first: 38, 41, 43, .. 53
     }
     // reload of token fragment mi; slot 1 brings the last block's fragment of THIS sub-step (its row is not
     // over when the others are reloaded), the others that of the next sub-step
@@ -295,7 +295,7 @@ template <int MB> struct Sched {
             if (MB == 4) return (s & 7) == 1 && s >= 9 ? (s >> 3) - 1 : -1;       // 9, 17, .. 57 -> 0 .. 6
             return (s & 7) == 2 && s >= 10 ? (s >> 3) - 1 : -1;                   // 10, 18, 26 -> 0 .. 2
         }
-        if (MB == 4) return s >= 38 && s <= 46 && !(s & 1) ? (s - 38) >> 1 : s == 48 ? 5 : s == 56 ? 6 : -1;
+        if (MB == 4) return s == 39 ? 0 : s >= 54 && s <= 59 ? s - 53 : -1;             // 39; 54 .. 59 -> 1 .. 6
         return s == 21 ? 0 : s == 30 ? 1 : s == 31 ? 2 : -1;
     }
     // copy number (0 .. 2*MB + 7) of the next slab pair
