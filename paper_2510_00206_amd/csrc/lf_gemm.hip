@@ -416,6 +416,36 @@ __device__ __forceinline__ bf16x8 zero_past_rank(bf16x8 v, int chunk, int valid_
     return __builtin_bit_cast(bf16x8, u);
 }
 
+// One 32-deep sub-step of t = dS A^T for the pair of block rows bp (operation (5), see block_store): MFMAs with a
+// vector-register destination, issued from assembly.  FIRST starts every chain on a zero input (its own statement
+// form, so that the later sub-steps need no test per MFMA).
+template <bool FIRST>
+__device__ __forceinline__ void lora_term_substep(f32x4 (&t)[2][8], int kk, int bp, const char* lds_tok, const char* lds_out,
+                                                  const FragLanes& fl, int rank_chunks, int l) {
+    const int chunk = 4 * kk + (l >> 4);
+    bf16x8 ft[2], fo[8];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+        ft[h] = zero_past_rank(__builtin_bit_cast(bf16x8, *(const u32x4*)(lds_tok + row_slab_off(l & 15, chunk) +
+                                                                            (2 * bp + h) * 2048)), chunk, rank_chunks);
+#pragma unroll
+    for (int ni = 0; ni < 8; ++ni) {
+        // contraction rows 32*kk + 8*(l >> 4) + {0..3 | 4..7} of the A slab
+        const int off = (fl.col_off ^ (ni << 5)) + kk * 16384;
+        fo[ni] = zero_past_rank(join_tr(lds_read_tr(lds_out, off), lds_read_tr(lds_out, off + 2048)), chunk, rank_chunks);
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int ni = 0; ni < 8; ++ni) {
+            // (s_nop 1: the operands may come straight from the vector ALU, see mfma_in_place)
+            if constexpr (FIRST)
+                asm volatile("s_nop 1\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=&v"(t[h][ni]) : "v"(fo[ni]), "v"(ft[h]));
+            else
+                asm volatile("s_nop 1\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(t[h][ni]) : "v"(fo[ni]), "v"(ft[h]));
+        }
+}
+
 // ---- the way out of a tile, two 16-row blocks of a wave's sub-tile at a time ---------------------------
 // Accumulator element e of block (mi, ni) in lane l is tile row  wm*32*MB + mi*16 + (l & 15)  and tile column
 // wn*128 + ni*16 + 4*(l >> 4) + e: a lane owns four consecutive columns of one row per block.  The 32 x 128 bf16
@@ -433,29 +463,9 @@ __device__ __forceinline__ void block_store(f32x4 (&acc)[2 * MB][8], int bp, con
     f32x4 t[2][8];
     if constexpr (LORA) {
         const int nkk = (rank_chunks + 3) >> 2;
+        lora_term_substep<true>(t, 0, bp, lds_tok, lds_out, fl, rank_chunks, l);
 #pragma unroll 1
-        for (int kk = 0; kk < nkk; ++kk) {
-            const int chunk = 4 * kk + (l >> 4);
-            bf16x8 ft[2], fo[8];
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-                ft[h] = zero_past_rank(__builtin_bit_cast(bf16x8, *(const u32x4*)(lds_tok + row_slab_off(l & 15, chunk) +
-                                                                                    (2 * bp + h) * 2048)), chunk, rank_chunks);
-#pragma unroll
-            for (int ni = 0; ni < 8; ++ni) {
-                // contraction rows 32*kk + 8*(l >> 4) + {0..3 | 4..7} of the A slab
-                const int off = (fl.col_off ^ (ni << 5)) + kk * 16384;
-                fo[ni] = zero_past_rank(join_tr(lds_read_tr(lds_out, off), lds_read_tr(lds_out, off + 2048)), chunk, rank_chunks);
-            }
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int ni = 0; ni < 8; ++ni) {
-                    // (s_nop 1: the operands may come straight from the vector ALU, see mfma_in_place)
-                    if (kk == 0) asm volatile("s_nop 1\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=&v"(t[h][ni]) : "v"(fo[ni]), "v"(ft[h]));
-                    else asm volatile("s_nop 1\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(t[h][ni]) : "v"(fo[ni]), "v"(ft[h]));
-                }
-        }
+        for (int kk = 1; kk < nkk; ++kk) lora_term_substep<false>(t, kk, bp, lds_tok, lds_out, fl, rank_chunks, l);
         // the compiler does not know that these were MFMAs: the distance the last result needs before the
         // vector ALU may read it is put in by hand
         asm volatile("s_nop 15\n\ts_nop 3"
