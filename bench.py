@@ -42,8 +42,8 @@ def measure_ceilings(torch, binding, dev, operands):
     """What this GPU sustains with nothing in the way (library diagnostics, timed with events on the launch
     stream): the GEMM kernels' MFMA instruction (and the other bf16 MFMA shape) in a register-resident loop on
     `operands` (values of the workload's distribution), one plain read of a 2 GiB buffer (eight times the memory-side cache), and
-    plain reads the size of `operands` (what one streaming kernel of the path reads), one launch each,
-    every launch on a window of the big buffer that no earlier launch of the series has touched."""
+    plain reads the size of `operands` (what one streaming kernel of the path reads), one launch each, back to
+    back, every launch on a window of the big buffer that has left the memory-side cache."""
     def timed(fn, reps, skip):
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
         evs[0].record()
@@ -67,12 +67,23 @@ def measure_ceilings(torch, binding, dev, operands):
     win = operands.numel() * operands.element_size() // 4096 * 4096
     nwin = min(16, (2 << 30) // win)
     wgs_win = 512                                # two workgroups per compute unit walk the window (the fastest shape found)
-    cursor = [0]
-
-    def read_window():
-        binding.ceiling_hbm_read(big[cursor[0] * win:(cursor[0] + 1) * win], sink2, wgs_win)
-        cursor[0] += 1
-    ms_win = timed(read_window, nwin, nwin // 4) if nwin >= 4 else None
+    views = [big[i * win:(i + 1) * win] for i in range(nwin)]
+    ms_win = None
+    if nwin >= 4:
+        # three whole-buffer reads go first so that the queue never runs dry while the host enqueues the windows
+        # (the events then bracket back-to-back launches, as they do inside a step); the big read ends on the far
+        # end of the buffer, the windows start at the near end, so none of them is in the memory-side cache
+        for _ in range(3):
+            read()
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(nwin + 1)]
+        evs[0].record()
+        for i in range(nwin):
+            binding.ceiling_hbm_read(views[i], sink2, wgs_win)
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(nwin)][nwin // 4:]
+        ms_win = sum(ms) / len(ms)
+    del views
     del big
 
     # the matrix loops last: the timed steps then start from the chip's state under its heaviest load
@@ -90,7 +101,7 @@ def measure_ceilings(torch, binding, dev, operands):
            "how": "register-resident MFMA loops, 256 accumulators per lane in independent chains, 1 wave per SIMD, operands = "
                   "the workload's X values: v_mfma_f32_16x16x32_bf16 (the GEMM kernels' instruction) and, for comparison, "
                   "v_mfma_f32_32x32x16_bf16; plain 16-byte-per-lane read of 2 GiB; the same read in single launches "
-                  "of sizeof(X) bytes on untouched windows"}
+                  "of sizeof(X) bytes, back to back, on windows that are not cached"}
     if ms_win:
         out["hbm_read_one_launch_gbs"] = round(win / (ms_win * 1e-3) / 1e9, 1)
         out["hbm_read_one_launch_us"] = round(ms_win * 1e3, 2)
