@@ -160,6 +160,14 @@ lora_status lora_debug_mask(int64_t M, int64_t K, float p, uint64_t seed, uint8_
  * settings; dA and dB are fp32 sums over the row panels and agree up to the order of those sums. */
 lora_status lora_set_row_tile(int32_t rows);
 
+/* Tuning knob and test hook (process-wide, not thread safe).  The GEMM kernels of operations (2) and (5)
+ * (Section 5.1) copy their operand slabs from global memory to LDS either one or two 64-deep slabs ahead of the
+ * matrix work.  By default every launch chooses (two ahead when the frozen weight is too large to stay cached -
+ * operation (5) - or the contraction is long enough - operation (2)).  slabs = 1 or 2 fixes the distance for all
+ * later launches, slabs = 0 restores the automatic choice; any other value returns LORA_ERR_PARAM.  Every output
+ * is bit-identical under all three settings. */
+lora_status lora_set_slab_lookahead(int32_t slabs);
+
 /* Diagnostic (host only, nothing is enqueued): the row-panel height the streaming reductions of operations
  * (3) / (4) (Section 5.1) would choose for an activation of C columns over these segments under the current
  * lora_set_row_tile setting, the number of panels that gives (each leaves one fp32 plane of partial dB or dA

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "liblorafusion_hip.so")
 
 EXPORTS = ("lora_fwd", "lora_bwd", "lora_bwd_noalloc", "multi_lora_fwd", "multi_lora_bwd", "multi_lora_fwd_ranked",
            "multi_lora_bwd_ranked", "lora_bwd_workspace_bytes",
-           "lora_debug_mask", "lora_status_string", "lora_version", "lora_set_row_tile", "lora_debug_stream_panels",
+           "lora_debug_mask", "lora_status_string", "lora_version", "lora_set_row_tile", "lora_set_slab_lookahead", "lora_debug_stream_panels",
            "lora_unfused_fwd", "lora_unfused_bwd", "lora_unfused_workspace_bytes")
 
 _lib = None
@@ -205,6 +205,11 @@ def lora_debug_mask(M, K, p, seed, device="cuda"):
 def lora_set_row_tile(rows: int):
     """0: automatic choice per launch; 128 / 256: the small / large height of the GEMM tiles and the down-projection workgroups."""
     _check(load_library().lora_set_row_tile(int(rows)))
+
+
+def lora_set_slab_lookahead(slabs: int):
+    """0: automatic choice per launch; 1 / 2: the GEMMs copy their operand slabs one / two slabs ahead of the matrix work."""
+    _check(load_library().lora_set_slab_lookahead(int(slabs)))
 
 
 PROF_KERNELS = ("down", "fwd_gemm", "ds_db", "finalize_ds_db", "da", "finalize_da", "dx_gemm")

@@ -338,6 +338,12 @@ lora_status lora_set_row_tile(int32_t rows) {
     return LORA_OK;
 }
 
+lora_status lora_set_slab_lookahead(int32_t slabs) {
+    if (slabs < 0 || slabs > 2) return LORA_ERR_PARAM;
+    force_slab_lookahead(slabs);
+    return LORA_OK;
+}
+
 lora_status lora_profile_begin(void) {
     for (ProfRec& r : g_prof) { (void)hipEventDestroy(r.beg); (void)hipEventDestroy(r.end); }
     g_prof.clear();

@@ -10,8 +10,8 @@
 // than one of 32x32x16 (half the accumulator traffic per flop), which decides the block shape.  A second
 // instantiation with 128 token rows per tile (4x8 blocks per wave) serves problems whose 256-row
 // tiling would leave compute units without a tile.  64-deep operand
-// slabs are copied global -> LDS without passing through registers, double-buffered, and the
-// rank-r LoRA term rides as extra contraction steps on the same accumulators.  (2) contracts over
+// slabs are copied global -> LDS without passing through registers, double-buffered, one or two slabs ahead
+// of the matrix work (see Sched), and the rank-r LoRA term rides as extra contraction steps on the same accumulators.  (2) contracts over
 // the contiguous dimension of both operands; (5) contracts over the row dimension of W (and of A),
 // which it reads from LDS with transposing loads so that no transposed copy of the frozen weight is
 // ever kept.
@@ -93,6 +93,9 @@ __device__ __forceinline__ uint32_t slab_m0(uint32_t lds_slab_addr) {
 }
 
 __device__ __forceinline__ void wait_slab_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// all copies but the N issued last have landed (loads of a wave complete in order; only valid while no stores
+// of the wave are outstanding)
+template <int N> __device__ __forceinline__ void wait_slab_loads_but() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 
 // Per-lane source offsets of one slab (bytes from the slab's first element), one per pass.
 struct SlabLanes { uint32_t off[PASSES]; };
@@ -272,25 +275,51 @@ __device__ __forceinline__ void read_frags(Frags<MB>& f, const char* lds_tok, co
     for (int mi = 0; mi < 2 * MB; ++mi) f.ft[mi] = read_tok_frag(lds_tok, fl, mi, 0);
 }
 
+// Where the copies of a slab step go.
+//  kCopySpread1 / kCopyEarly1: the step copies the NEXT slab pair into the other LDS stage during its sub-step 0
+//   (spread over the whole sub-step, or as early as the reads allow) and hands over late in sub-step 1.
+//  kCopyAhead2: the copies run TWO slabs ahead.  All fragments of a slab have been read by slot 1 of its
+//   sub-step 1, so the hand-over moves to the start of sub-step 1 (the slab after this one has landed; this
+//   slab's stage is free) and the copies of the slab after next follow it, into the stage the step is still
+//   computing from registers on.  A copy then has a whole step to land instead of about two thirds of one,
+//   which is worth 5 - 8 % of either GEMM when the weight streams from HBM, and 2.5 % of operation (2) when it
+//   does not.
+constexpr int kCopySpread1 = 0, kCopyEarly1 = 1, kCopyAhead2 = 2;
+
 // What rides on MFMA slot s of sub-step `sub` (s = 8 * token block + out block; -1: nothing).
 template <int MB> struct Sched {
     static constexpr int TB = 2 * MB, SS = 8 * TB;
-    static constexpr int HO = MB == 4 ? 36 : 20;          // sub-step 1: hand-over after this slot
+    // sub-step 1: hand-over after this slot
+    static constexpr int ho(int mode) { return mode == kCopyAhead2 ? (MB == 4 ? 7 : 3) : (MB == 4 ? 36 : 20); }
+    static constexpr int find(const int* at, int n, int s) {
+        for (int j = 0; j < n; ++j)
+            if (at[j] == s) return j;
+        return -1;
+    }
     // read of out fragment k for the next sub-step (sub-step 0: of this slab; sub-step 1: of the next slab)
-    static constexpr int fo_read(int sub, int s) {
+    static constexpr int fo_read(int sub, int s, int mode) {
         if (sub == 0) return MB == 4 ? ((s & 7) == 4 ? s >> 3 : -1) : ((s & 3) == 0 ? s >> 2 : -1);
+        if (mode == kCopyAhead2) {
+            constexpr int at4[8] = {12, 15, 19, 22, 28, 31, 35, 38}, at2[8] = {18, 19, 20, 21, 22, 23, 24, 26};
+            return find(MB == 4 ? at4 : at2, 8, s);
+        }
         if (MB == 4) return s == 37 ? 0 : s >= 40 && s <= 52 && !(s & 1) ? (s - 38) >> 1 : -1;      // 37, 40, 42, .. 52 (in the order of their first use)
-        return s >= HO + 2 && s <= HO + 9 ? s - HO - 2 : -1;                                      // 22 .. 29
+        return s >= 22 && s <= 29 ? s - 22 : -1;
     }
     // column slab, 256-row tile: the second transposing read of out fragment k (the first rides on fo_read's slot)
-    static constexpr int fo_read_hi(int sub, int s) {
+    static constexpr int fo_read_hi(int sub, int s, int mode) {
         if (sub == 0) return (s & 7) == 5 ? s >> 3 : -1;
+        if (mode == kCopyAhead2) {
+            constexpr int at4[8] = {13, 16, 20, 23, 29, 32, 36, 39};
+            return find(at4, 8, s);
+        }
         return s == 38 ? 0 : s >= 41 && s <= 53 && (s & 1) ? (s - 39) >> 1 : -1;    // right after the first: 38, 41, 43, .. 53
     }
     // reload of token fragment mi; slot 1 brings the last block's fragment of THIS sub-step (its row is not
     // over when the others are reloaded), the others that of the next sub-step
-    static constexpr int ft_read(int sub, int s) {
+    static constexpr int ft_read(int sub, int s, int mode) {
         if (s == 1) return TB - 1;
+        if (sub == 1 && mode == kCopyAhead2) return (s & 7) == 1 && s >= 9 ? (s >> 3) - 1 : -1;   // as soon as the block row is over
         if (sub == 0) {
             if (MB == 4) return (s & 7) == 1 && s >= 9 ? (s >> 3) - 1 : -1;       // 9, 17, .. 57 -> 0 .. 6
             return (s & 7) == 2 && s >= 10 ? (s >> 3) - 1 : -1;                   // 10, 18, 26 -> 0 .. 2
@@ -298,27 +327,27 @@ template <int MB> struct Sched {
         if (MB == 4) return s == 39 ? 0 : s >= 54 && s <= 59 ? s - 53 : -1;             // 39; 54 .. 59 -> 1 .. 6
         return s == 21 ? 0 : s == 30 ? 1 : s == 31 ? 2 : -1;
     }
-    // copy number (0 .. 2*MB + 7) of the next slab pair
-    // mode 1: as early as the reads allow - the last copies then have the longest to land, which counts when the
-    // operands come from HBM; mode 0: spread over the whole sub-step (operation (5), whose slots also carry the
-    // transposing reads, is faster with this); mode 2: as dense as mode 1 but a quarter of a sub-step later (the
-    // even waves of operation (2) when the waves of a workgroup take turns, see fwd_gemm_kernel)
+    // copy number (0 .. 2*MB + 7) of the slab pair the step brings.  Operation (5), whose slots also carry the
+    // transposing reads, wants its copies spread out whichever way they run; operation (2) wants them early when
+    // they run one slab ahead (the last ones then have the longest to land) and spread when they run two ahead.
     static constexpr int copy_at(int sub, int s, int mode) {
+        if (mode == kCopyAhead2) {
+            if (sub != 1) return -1;
+            constexpr int at4[16] = {8, 11, 14, 18, 21, 24, 27, 30, 34, 37, 40, 43, 46, 50, 53, 56};
+            constexpr int at2[12] = {4, 5, 6, 7, 8, 10, 11, 12, 13, 14, 15, 16};
+            return MB == 4 ? find(at4, 16, s) : find(at2, 12, s);
+        }
         if (sub != 0) return -1;
-        if (MB == 4 && mode == 0) return (s & 3) == 2 ? s >> 2 : -1;                               // 2, 6, .. 62 -> 0 .. 15
-        if (MB == 4 && mode == 2)                                                                  // 18,19,22,23, .. 46,47
-            return s >= 16 && s < 48 && (s & 2) ? ((s - 16) >> 3) * 4 + (s & 1) + ((s & 4) >> 1) : -1;
+        if (MB == 4 && mode == kCopySpread1) return (s & 3) == 2 ? s >> 2 : -1;                  // 2, 6, .. 62 -> 0 .. 15
         if (MB == 4) return s < 32 && (s & 2) ? (s >> 3) * 4 + (s & 1) + ((s & 4) >> 1) : -1;   // 2,3,6,7, 10,11,.. -> 0 .. 15
         // 128-row tile: slots 2 .. 19 that carry no read
         constexpr int at[12] = {2, 3, 5, 6, 7, 9, 11, 13, 14, 15, 17, 19};
-        for (int j = 0; j < 12; ++j)
-            if (at[j] == s) return j;
-        return -1;
+        return find(at, 12, s);
     }
 };
 
 // (operation (5) hangs its hash pieces on free slots; nothing for the others)
-template <int MB, int SUB, int S> __device__ __forceinline__ void shadow_slot(NoShadow&) {}
+template <int MB, int SUB, int S, int MODE> __device__ __forceinline__ void shadow_slot(NoShadow&) {}
 
 // LDS side of one slab step: where the current slab pair lies and where the next one goes.
 struct StepLds {
@@ -326,14 +355,14 @@ struct StepLds {
     const char* nxt_tok; const char* nxt_out;     // ... and in the slabs being filled
 };
 
-template <bool COL_SLAB, int MB, int S, int EARLY, class SH>
+template <bool COL_SLAB, int MB, int S, int MODE, class SH>
 __device__ __forceinline__ void slots(f32x4 (&acc)[2 * MB][8], Frags<MB>& f, const StepLds& L, const FragLanes& fl,
                                         const NextSlabs& nx, bool read_next, SH& sh, Pipe& pp) {
     using SC = Sched<MB>;
     constexpr int sub = S / SC::SS, s = S % SC::SS, mi = s >> 3, ni = s & 7;
     acc[mi][ni] = LF_MFMA(f.fo[sub][ni], f.ft[mi], acc[mi][ni]);
     constexpr bool SPLIT = COL_SLAB && MB == 4;      // the two halves of an out fragment on two slots
-    constexpr int k = SC::fo_read(sub, s);
+    constexpr int k = SC::fo_read(sub, s, MODE);
     if constexpr (k >= 0 && !SPLIT) {
         if constexpr (sub == 0) f.fo[1][k] = read_out_frag<COL_SLAB>(L.cur_out, fl, k, 1);
         else if (read_next) f.fo[0][k] = read_out_frag<COL_SLAB>(L.nxt_out, fl, k, 0);
@@ -342,47 +371,51 @@ __device__ __forceinline__ void slots(f32x4 (&acc)[2 * MB][8], Frags<MB>& f, con
         if constexpr (sub == 0) read_out_frag_half<0>(f.fo[1][k], L.cur_out, fl, k, 1);
         else if (read_next) read_out_frag_half<0>(f.fo[0][k], L.nxt_out, fl, k, 0);
     }
-    constexpr int kh = SPLIT ? SC::fo_read_hi(sub, s) : -1;
+    constexpr int kh = SPLIT ? SC::fo_read_hi(sub, s, MODE) : -1;
     if constexpr (kh >= 0) {
         if constexpr (sub == 0) read_out_frag_half<1>(f.fo[1][kh], L.cur_out, fl, kh, 1);
         else if (read_next) read_out_frag_half<1>(f.fo[0][kh], L.nxt_out, fl, kh, 0);
     }
-    constexpr int m = SC::ft_read(sub, s);
+    constexpr int m = SC::ft_read(sub, s, MODE);
     if constexpr (m >= 0) {
         if constexpr (s == 1) f.ft[m] = read_tok_frag(L.cur_tok, fl, m, sub);
         else if constexpr (sub == 0) f.ft[m] = read_tok_frag(L.cur_tok, fl, m, 1);
         else if (read_next) f.ft[m] = read_tok_frag(L.nxt_tok, fl, m, 0);
     }
-    constexpr int j = SC::copy_at(sub, s, EARLY);
+    constexpr int j = SC::copy_at(sub, s, MODE);
     if constexpr (j >= 0) issue_copy<MB, j>(nx);
-    shadow_slot<MB, sub, s>(sh);
+    shadow_slot<MB, sub, s, MODE>(sh);
     if constexpr (sub == 1 && s == 0) {
         // every copy of this step has been issued: the sources move on to the slab pair after
         pp.src_tok += pp.adv_tok;
         pp.src_out += pp.adv_out;
     }
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (sub == 1 && s == SC::HO) {
-        wait_slab_loads();
+    if constexpr (sub == 1 && s == SC::ho(MODE)) {
+        // two ahead: the copies that follow overwrite the stage this wave has just read its last fragments from,
+        // so those reads are waited for, too, before the barrier lets the other waves' copies go
+        if constexpr (MODE == kCopyAhead2) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        else wait_slab_loads();
         __syncthreads();
     }
-    if constexpr (S + 1 < 2 * SC::SS) slots<COL_SLAB, MB, S + 1, EARLY>(acc, f, L, fl, nx, read_next, sh, pp);
+    if constexpr (S + 1 < 2 * SC::SS) slots<COL_SLAB, MB, S + 1, MODE>(acc, f, L, fl, nx, read_next, sh, pp);
 }
 
 // One 64-deep slab pair: two sub-steps of 16*MB MFMAs; the copies of the next slab pair ride on sub-step 0,
 // the hand-over (copies landed, workgroup barrier) sits in sub-step 1 and is followed by the first fragment
 // reads of the next slab (if read_next).  On entry f holds the fragments of sub-step 0 of the current slab.
-template <bool COL_SLAB, int MB, int EARLY = 0, class SH>
+template <bool COL_SLAB, int MB, int MODE, class SH>
 __device__ __forceinline__ void slab_step(f32x4 (&acc)[2 * MB][8], Frags<MB>& f, const char* lds_tok_org,
                                             const char* lds_out_org, CopyOrg lds_copy_org, const FragLanes& fl, Pipe& pp,
                                             const SlabLanes& lanes_tok, const SlabLanes& lanes_out, bool copy_next,
                                             bool read_next, SH& sh) {
     const uint32_t nxt = STAGE_BYTES - pp.rd;
     const StepLds L{lds_tok_org + pp.rd, lds_out_org + pp.rd, lds_tok_org + nxt, lds_out_org + nxt};
-    const NextSlabs nx{pp.src_tok, pp.src_out, lanes_tok, lanes_out, lds_copy_org.tok + nxt, lds_copy_org.out + nxt,
+    const uint32_t dst = MODE == kCopyAhead2 ? pp.rd : nxt;     // two ahead: into the stage being computed on, once it is free
+    const NextSlabs nx{pp.src_tok, pp.src_out, lanes_tok, lanes_out, lds_copy_org.tok + dst, lds_copy_org.out + dst,
                        copy_next};
     __builtin_amdgcn_sched_barrier(0);
-    slots<COL_SLAB, MB, 0, EARLY>(acc, f, L, fl, nx, read_next, sh, pp);
+    slots<COL_SLAB, MB, 0, MODE>(acc, f, L, fl, nx, read_next, sh, pp);
     pp.rd = nxt;
 }
 
@@ -512,8 +545,10 @@ __device__ __forceinline__ void block_store(f32x4 (&acc)[2 * MB][8], int bp, con
 
 
 // ---- operation (2): Y = X W + S' B ---------------------------------------------------------------
-template <int MB, int EARLY>
-__device__ __forceinline__ void fwd_gemm_body(const FwdGemmArgs& p) {
+// LA: how many slabs ahead of the matrix work the copies run (1 or 2).
+template <int MB, int LA>
+__global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
+    constexpr int MODE = LA == 2 ? kCopyAhead2 : kCopyEarly1;
     constexpr int BM = 64 * MB, TB = 2 * MB;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int total = p.tiles_m * p.tiles_n;
@@ -539,6 +574,13 @@ __device__ __forceinline__ void fwd_gemm_body(const FwdGemmArgs& p) {
         load_slab<2 * MB>(lds0, p.X + (int64_t)tc.rt.row_start * p.K, sx);
         load_slab(lds0 + TILE_BYTES, p.W + (int64_t)tc.c0 * p.K, sw);
     }
+    constexpr int D = LA;                            // how many slabs ahead the copies run
+    bool second_on_its_way = false;                  // first tile only: the main loop starts on the first slab pair alone
+    if (D == 2 && nk > 1) {
+        load_slab<2 * MB>(lds0 + STAGE_BYTES, p.X + (int64_t)tc.rt.row_start * p.K + BK, sx);
+        load_slab(lds0 + STAGE_BYTES + TILE_BYTES, p.W + (int64_t)tc.c0 * p.K + BK, sw);
+        second_on_its_way = true;
+    }
     for (;;) {
         const RowTile rt = tc.rt;
         const GroupMap gm = tc.gm;
@@ -554,25 +596,29 @@ __device__ __forceinline__ void fwd_gemm_body(const FwdGemmArgs& p) {
         }
         f32x4 acc[TB][8];
         zero_acc<MB>(acc);                           // while the first slabs are on their way (first tile)
-        wait_slab_loads();
+        if (second_on_its_way) wait_slab_loads_but<2 * MB + PASSES>();
+        else wait_slab_loads();
+        second_on_its_way = false;
         __syncthreads();
         Frags<MB> f;
         if (nk > 0) read_frags<false, MB>(f, smem + pp.rd + tok_org, smem + pp.rd + out_org, fl);
-        pp.src_tok = (const char*)(Xt + BK) - kCopyBias;
-        pp.src_out = (const char*)(Wt + BK) - kCopyBias;
-        for (int kt = 0; kt + 1 < nk; ++kt)
-            slab_step<false, MB, EARLY>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, sx, sw, true, true, none);
+        pp.src_tok = (const char*)(Xt + D * BK) - kCopyBias;
+        pp.src_out = (const char*)(Wt + D * BK) - kCopyBias;
+        for (int kt = 0; kt + D < nk; ++kt)          // step kt brings slab kt + D
+            slab_step<false, MB, MODE>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, sx, sw, true, true, none);
         // the lane offsets of the LoRA slab pair are formed only now: through the main loop they would cost
         // sixteen registers that it does not have
         const SlabLanes ss = row_slab_lanes<2 * MB>(rr, rt.rows, rr >> 3), sb = row_slab_lanes(rr, cols_valid, rr >> 3);
-        if (nk > 0) {
-            // after the last base slab the LoRA step rides as one more slab: token operand S' [rows, r],
-            // out operand B [N, r]
-            pp.src_tok = (const char*)Ssrc - kCopyBias;
-            pp.src_out = (const char*)Bsrc - kCopyBias;
-            slab_step<false, MB, EARLY>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sb,
-                                   has_lora && !gm.mixed, false, none);
-        }
+        // after the last base slab the LoRA step rides as one more slab (token operand S' [rows, r], out operand
+        // B [N, r]): the last base step brings it or, two ahead, the last but one (the last then brings nothing)
+        const bool lora_piped = has_lora && !gm.mixed && nk >= D;
+        pp.src_tok = (const char*)Ssrc - kCopyBias;
+        pp.src_out = (const char*)Bsrc - kCopyBias;
+        if (D == 2 && nk > 1)
+            slab_step<false, MB, MODE>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sb, lora_piped, true, none);
+        if (nk > 0)
+            slab_step<false, MB, MODE>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sb, D == 1 && lora_piped,
+                                        false, none);
         const uint32_t lo = pp.rd;                     // the stage that holds (or receives) the LoRA slab pair
 
         // The next tile of this workgroup: its first slab pair is asked for now, into the stage that the last
@@ -591,6 +637,7 @@ __device__ __forceinline__ void fwd_gemm_body(const FwdGemmArgs& p) {
                 load_slab(lds0 + (STAGE_BYTES - lo) + TILE_BYTES, p.W + (int64_t)tc.c0 * p.K, sw);
             }
         }
+        const bool lora_sync = gm.mixed || (D == 2 && nk == 1);          // the LoRA slab pair is fetched here, not by the pipeline (nk == 0: at the top)
 
         if (has_lora) {
             // One pass per adapter present in the tile: a single one unless the tile is mixed (FusedMultiLoRA
@@ -602,7 +649,7 @@ __device__ __forceinline__ void fwd_gemm_body(const FwdGemmArgs& p) {
 #pragma unroll 1
             for (int q = 0; q < ngroups; ++q) {
                 const int g = group_adapter(gm, q);
-                if (gm.mixed) {
+                if (lora_sync) {
                     __syncthreads();                   // every wave is done with the stage's previous contents
                     if (q == 0) load_slab<2 * MB>(lds0 + lo, Ssrc, ss);
                     load_slab(lds0 + lo + TILE_BYTES, p.B + ((int64_t)g * p.N + n0) * p.r, sb);
@@ -633,6 +680,12 @@ __device__ __forceinline__ void fwd_gemm_body(const FwdGemmArgs& p) {
             }
             mfma_in_place_done();
         }
+        if (D == 2 && has_next && nk > 1) {
+            // the next tile's second slab pair, into the stage of the LoRA slab pair once every wave has left it
+            __syncthreads();
+            load_slab<2 * MB>(lds0 + lo, p.X + (int64_t)tc.rt.row_start * p.K + BK, sx);
+            load_slab(lds0 + lo + TILE_BYTES, p.W + (int64_t)tc.c0 * p.K + BK, sw);
+        }
 
         // way out, pair of block rows by pair, through the wave's own 8 KB
         {
@@ -652,19 +705,6 @@ __device__ __forceinline__ void fwd_gemm_body(const FwdGemmArgs& p) {
         id = next;
         pp.rd = STAGE_BYTES - lo;
     }
-}
-
-// The four waves of a workgroup run in lockstep (one barrier per slab step), so whatever they do in the same
-// slot they do at the same time; when all four issue their copies together, the hand-over costs 5 % of the
-// kernel as long as the operands come from the caches (taking out either its wait or its barrier gives that
-// back - it is the joint arrival that costs).  STAG: odd waves issue their copies early in the step and even
-// waves in its middle: two instantiations of the whole body that never meet again (a branch that rejoined
-// would have to merge the accumulators); every wave passes the same barriers in either.  With operands that
-// stream from HBM the copies need all the time they can get: then every wave issues them early.
-template <int MB, bool STAG>
-__global__ void __launch_bounds__(NTHREADS) fwd_gemm_kernel(FwdGemmArgs p) {
-    if (!STAG || (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) & 1)) fwd_gemm_body<MB, 1>(p);
-    else fwd_gemm_body<MB, 2>(p);
 }
 
 // ---- dropout keep flags formed in the shadow of the matrix work (operation (5)) ---------------------
@@ -717,9 +757,27 @@ __device__ __forceinline__ void keep_piece(KeepShadow& k) {
 }
 
 // pieces ride on slots 2 .. 6*WPS+1 of sub-step 1 (before the hand-over; slot 1 carries a fragment read)
-template <int MB, int SUB, int S> __device__ __forceinline__ void shadow_slot(KeepShadow& k) {
+// (copies two slabs ahead: those slots carry the copies; the pieces ride on the slots of sub-step 0 that carry no read)
+template <int MB> constexpr int shadow_piece_pf2(int s) {
+    if (MB == 4) {
+        constexpr int at[24] = {2, 3, 6, 7, 8, 10, 11, 14, 15, 16, 18, 19, 22, 23, 24, 26, 27, 30, 31, 32, 34, 35, 38, 39};
+        for (int j = 0; j < 24; ++j)
+            if (at[j] == s) return j;
+        return -1;
+    }
+    constexpr int at[12] = {2, 3, 5, 6, 7, 9, 11, 13, 14, 15, 17, 19};
+    for (int j = 0; j < 12; ++j)
+        if (at[j] == s) return j;
+    return -1;
+}
+template <int MB, int SUB, int S, int MODE> __device__ __forceinline__ void shadow_slot(KeepShadow& k) {
     constexpr int WPS = MB == 4 ? 4 : 2;
-    if constexpr (SUB == 1 && S >= 2 && S < 2 + 6 * WPS) keep_piece<WPS, S - 2>(k);
+    if constexpr (MODE != kCopyAhead2) {
+        if constexpr (SUB == 1 && S >= 2 && S < 2 + 6 * WPS) keep_piece<WPS, S - 2>(k);
+    } else if constexpr (SUB == 0) {
+        constexpr int pid = shadow_piece_pf2<MB>(S);
+        if constexpr (pid >= 0) keep_piece<WPS, pid>(k);
+    }
 }
 // the same pieces outside any slab step (tiles with fewer than 32 slab steps)
 template <int WPS, int PID = 0>
@@ -749,8 +807,10 @@ __device__ __forceinline__ SlabLanes col_slab_lanes(int64_t ld, int rows_valid, 
 // product first, while the keep flags of the tile are formed in the shadow of its MFMAs; the LoRA slab
 // pair [dS | A] rides in as one more slab during the last base slab, and the masked LoRA term is added
 // pair of block rows by pair on the way out.  p.N == 0 (LoRA term only) serves the unfused baseline.
-template <int MB, bool LORA>
+template <int MB, bool LORA, int LA>
 __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
+    constexpr int CM = LA == 2 ? kCopyAhead2 : kCopySpread1;
+    constexpr bool PF = LA == 2;                      // copies two slabs ahead (LA as in fwd_gemm_kernel)
     constexpr int BM = 64 * MB, TB = 2 * MB;
     constexpr int WPS = MB == 4 ? 4 : 2;             // hash words per slab step and lane
     constexpr int FLAG_STEPS = 16 * TB / WPS;        // slab steps until the tile's flags are complete: 32
@@ -787,10 +847,15 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
     if (nk > 0) {
         load_slab<2 * MB>(lds0, dYt + 0, sd);
         load_slab(lds0 + TILE_BYTES, Wt, sw);
-    } else if (LORA) {
+    }
+    if (PF && nk > 1) {                              // copies run two slabs ahead
+        load_slab<2 * MB>(lds0 + STAGE_BYTES, dYt + BK, sd);
+        load_slab(lds0 + STAGE_BYTES + TILE_BYTES, Wt + (int64_t)BK * p.K, sw);
+    }
+    if (LORA && (nk == 0 || (PF && nk == 1))) {
         const SlabLanes ss = row_slab_lanes<2 * MB>(rr, rt.rows, rr >> 3), sa = col_slab_lanes(p.K, rr, cols_valid);
-        load_slab<2 * MB>(lds0, dSt, ss);
-        load_slab(lds0 + TILE_BYTES, At, sa);
+        load_slab<2 * MB>(lds0 + lo, dSt, ss);
+        load_slab(lds0 + lo + TILE_BYTES, At, sa);
     }
     zero_acc<MB>(acc);                               // while the first slabs are on their way
 
@@ -829,38 +894,48 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
         ks.x[0] = ks.x[1] = ks.t[0] = ks.t[1] = 0;
     }
 
-    wait_slab_loads();
+    // (two slab pairs on their way: the main loop starts on the first alone)
+    if (PF && (nk > 1 || (nk == 1 && LORA))) wait_slab_loads_but<2 * MB + PASSES>();
+    else wait_slab_loads();
     __syncthreads();
     Frags<MB> f;
     if (nk > 0) read_frags<true, MB>(f, smem + tok_org, smem + out_org, fl);
     const CopyOrg corg = copy_org<MB>(lds0);
-    // slab steps 0 .. nk-2 bring the next base slab pair; the first 32 of all steps also carry the hash pieces
-    Pipe pp{(const char*)(dYt + BK) - kCopyBias, (const char*)(Wt + (int64_t)BK * p.K) - kCopyBias, BK * 2, (int64_t)BK * p.K * 2, 0u};
+    // slab steps bring the next base slab pair (PF: the one after next); the first 32 of all steps also carry the
+    // hash pieces.  D = how far ahead the copies run.
+    constexpr int D = PF ? 2 : 1;
+    Pipe pp{(const char*)(dYt + D * BK) - kCopyBias, (const char*)(Wt + (int64_t)D * BK * p.K) - kCopyBias, BK * 2,
+            (int64_t)BK * p.K * 2, 0u};
     int kt = 0;
     if constexpr (LORA) {
-        for (; kt < min(nk - 1, FLAG_STEPS); ++kt) {
+        for (; kt < min(nk - D, FLAG_STEPS); ++kt) {
             keep_step_begin(kt);
-            slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, sd, sw, true, true, ks);
+            slab_step<true, MB, CM>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, sd, sw, true, true, ks);
             keep_step_end(kt);
         }
     }
-    for (; kt < nk - 1; ++kt)
-        slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, sd, sw, true, true, none);
+    for (; kt < nk - D; ++kt)
+        slab_step<true, MB, CM>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, sd, sw, true, true, none);
     if (nk > 0) {
-        // the last base slab: the LoRA slab pair [dS | A] rides in as one more slab (nothing if there is no
+        // the last D base slabs: the LoRA slab pair [dS | A] rides in as one more slab (nothing if there is no
         // LoRA term); its lane offsets are formed only now, the main loop has no registers for them
         const SlabLanes ss = row_slab_lanes<2 * MB>(rr, rt.rows, rr >> 3), sa = col_slab_lanes(p.K, rr, cols_valid);
         pp.src_tok = (const char*)dSt - kCopyBias;
         pp.src_out = (const char*)At - kCopyBias;
-        if constexpr (LORA) {
-            // one code path for this step whatever kt is (two would have to merge all the accumulators):
-            // past the 32nd step the hash pieces still run, on a step number that is never flushed
-            const bool forming = kt < FLAG_STEPS;
-            if (forming) keep_step_begin(kt);
-            slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sa, true, false, ks);
-            if (forming) keep_step_end(kt);
-        } else {
-            slab_step<true, MB>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sa, false, false, none);
+        // step nk - D brings the LoRA slab pair; with D = 2 the last step brings nothing
+#pragma unroll 1
+        for (; kt < nk; ++kt) {
+            const bool bring = LORA && kt == nk - D, last = kt == nk - 1;
+            if constexpr (LORA) {
+                // one code path for these steps whatever kt is (two would have to merge all the accumulators):
+                // past the 32nd step the hash pieces still run, on a step number that is never flushed
+                const bool forming = kt < FLAG_STEPS;
+                if (forming) keep_step_begin(kt);
+                slab_step<true, MB, CM>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sa, bring, !last, ks);
+                if (forming) keep_step_end(kt);
+            } else {
+                slab_step<true, MB, CM>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sa, bring, !last, none);
+            }
         }
     }
     if constexpr (LORA) {
@@ -971,6 +1046,13 @@ static hipError_t launch_gemm(K kernel, bool& attr_set, const A& a, hipStream_t 
     return hipGetLastError();
 }
 
+static std::atomic<int> g_forced_lookahead{0};      // 0: chosen per launch; 1 or 2: fixed (tuning and tests)
+void force_slab_lookahead(int slabs) { g_forced_lookahead.store(slabs, std::memory_order_relaxed); }
+
+// A frozen weight of up to 64 MB stays in the 256 MB memory-side cache beside the activations; a larger one
+// streams from HBM in every launch.
+static bool weight_streams(int64_t K, int64_t N) { return K * N * 2 > (64ll << 20); }
+
 hipError_t launch_fwd_gemm(FwdGemmArgs a, int forced, hipStream_t st) {
     a.tiles_n = (a.N + BN - 1) / BN;
     const RowTiling t = plan_row_tiles(a.tb, a.M, a.tiles_n, forced);
@@ -978,14 +1060,15 @@ hipError_t launch_fwd_gemm(FwdGemmArgs a, int forced, hipStream_t st) {
     a.tiles_m = t.tiles_m;
     if (a.tiles_m == 0) return hipSuccess;
     static bool attr_set[4] = {false, false, false, false};
-    // a frozen weight of up to 64 MB stays in the 256 MB memory-side cache beside the activations: the waves
-    // then take turns with their copies (measured: 2 % faster at K = N = 4096, 2 - 5 % slower with 117 and 470 MB)
-    const bool stag = (int64_t)a.K * a.N * 2 <= (64ll << 20);
+    // copies two slabs ahead unless the contraction is short (measured: 2.5 % faster at K = N = 4096, 5 - 8 % with
+    // weights of 117 and 470 MB; a contraction of 16 slabs, where every step waits for its copies anyway, 4 % slower)
+    const int knob = g_forced_lookahead.load(std::memory_order_relaxed);
+    const bool ahead2 = knob ? knob == 2 : a.K >= 32 * BK;
     if (t.bm == 256)
-        return stag ? launch_gemm(fwd_gemm_kernel<4, true>, attr_set[0], a, st, GEMM_LDS_TOTAL, true)
-                    : launch_gemm(fwd_gemm_kernel<4, false>, attr_set[1], a, st, GEMM_LDS_TOTAL, true);
-    return stag ? launch_gemm(fwd_gemm_kernel<2, true>, attr_set[2], a, st, GEMM_LDS_TOTAL, true)
-                : launch_gemm(fwd_gemm_kernel<2, false>, attr_set[3], a, st, GEMM_LDS_TOTAL, true);
+        return ahead2 ? launch_gemm(fwd_gemm_kernel<4, 2>, attr_set[0], a, st, GEMM_LDS_TOTAL, true)
+                      : launch_gemm(fwd_gemm_kernel<4, 1>, attr_set[1], a, st, GEMM_LDS_TOTAL, true);
+    return ahead2 ? launch_gemm(fwd_gemm_kernel<2, 2>, attr_set[2], a, st, GEMM_LDS_TOTAL, true)
+                  : launch_gemm(fwd_gemm_kernel<2, 1>, attr_set[3], a, st, GEMM_LDS_TOTAL, true);
 }
 
 hipError_t launch_bwd_dx(DxGemmArgs a, int forced, hipStream_t st) {
@@ -994,13 +1077,25 @@ hipError_t launch_bwd_dx(DxGemmArgs a, int forced, hipStream_t st) {
     a.uniform_tiles = t.uniform;
     a.tiles_m = t.tiles_m;
     if (a.tiles_m == 0) return hipSuccess;
-    static bool attr_set[4] = {false, false, false, false};
+    static bool attr_set[8] = {false, false, false, false, false, false, false, false};
+    // copies two slabs ahead when the weight streams from HBM (measured: 3 - 7 % faster there, 0.5 - 1 % slower
+    // with a cache-resident weight, whose copies land in time anyway)
+    const int knob = g_forced_lookahead.load(std::memory_order_relaxed);
+    const bool ahead2 = knob ? knob == 2 : weight_streams(a.K, a.N);
     // with a LoRA term: the slab stages plus the parked keep flags (2 * MB words per lane)
-    if (a.r > 0)
-        return t.bm == 256 ? launch_gemm(bwd_dx_kernel<4, true>, attr_set[0], a, st, GEMM_LDS_BYTES + 8 * NTHREADS * 4)
-                           : launch_gemm(bwd_dx_kernel<2, true>, attr_set[1], a, st, GEMM_LDS_BYTES + 4 * NTHREADS * 4);
-    return t.bm == 256 ? launch_gemm(bwd_dx_kernel<4, false>, attr_set[2], a, st)
-                       : launch_gemm(bwd_dx_kernel<2, false>, attr_set[3], a, st);
+    const int lds4 = GEMM_LDS_BYTES + 8 * NTHREADS * 4, lds2 = GEMM_LDS_BYTES + 4 * NTHREADS * 4;
+    if (a.r > 0) {
+        if (t.bm == 256)
+            return ahead2 ? launch_gemm(bwd_dx_kernel<4, true, 2>, attr_set[0], a, st, lds4)
+                          : launch_gemm(bwd_dx_kernel<4, true, 1>, attr_set[1], a, st, lds4);
+        return ahead2 ? launch_gemm(bwd_dx_kernel<2, true, 2>, attr_set[2], a, st, lds2)
+                      : launch_gemm(bwd_dx_kernel<2, true, 1>, attr_set[3], a, st, lds2);
+    }
+    if (t.bm == 256)
+        return ahead2 ? launch_gemm(bwd_dx_kernel<4, false, 2>, attr_set[4], a, st)
+                      : launch_gemm(bwd_dx_kernel<4, false, 1>, attr_set[5], a, st);
+    return ahead2 ? launch_gemm(bwd_dx_kernel<2, false, 2>, attr_set[6], a, st)
+                  : launch_gemm(bwd_dx_kernel<2, false, 1>, attr_set[7], a, st);
 }
 
 }  // namespace lf

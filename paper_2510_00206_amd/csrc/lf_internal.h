@@ -62,6 +62,8 @@ constexpr int kStreamChunk = 512;    // column-chunk width of the streaming kern
 
 void force_row_tile(int rows);        // 0 (automatic), or the small (128) / large (256) height of every kernel that has two
 int forced_row_tile();                // an entry point reads this ONCE and hands the value to everything it launches
+void force_slab_lookahead(int slabs); // 0 (automatic), or how many slabs ahead the GEMMs' copies run (1 or 2); read per GEMM launch,
+                                      // results do not depend on it
 
 // Rows per panel of a streaming reduction over a [M, C] activation.  Every panel leaves an fp32 partial
 // of C x r (dB) or r x C (dA) values, so taller panels mean less partial traffic, while a launch with

@@ -35,6 +35,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_version_and_status_strings(lib):
     assert lib.lora_version() >= 100
     assert [lib.lora_set_row_tile(v) for v in (128, 256, 64, -1, 0)] == [0, 0, 4, 4, 0]
+    assert [lib.lora_set_slab_lookahead(v) for v in (1, 2, 3, -1, 0)] == [0, 0, 4, 4, 0]
     assert lib.lora_status_string(0) == b"ok"
     for code in range(1, 9):
         assert len(lib.lora_status_string(code)) > 3

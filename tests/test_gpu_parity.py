@@ -11,16 +11,21 @@ from gpu_util import TOL, compare, f64, rel_err, run_gpu, run_oracle
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module", autouse=True, params=[256, 128], ids=["tile256", "tile128"])
+@pytest.fixture(scope="module", autouse=True, params=[(256, 1), (128, 1), (256, 2), (128, 2)],
+                ids=["tile256-ahead1", "tile128-ahead1", "tile256-ahead2", "tile128-ahead2"])
 def _lib(request):
     """Every test of this module runs with the large and with the small height of the kernels that
     have two (GEMM tiles of 256 / 128 rows, down-projection workgroups of 32 / 16 rows) fixed: small
-    shapes would otherwise all take the small one.  The automatic choice is what the full-size tests run."""
+    shapes would otherwise all take the small one; and with the GEMMs' slab copies one and two slabs ahead
+    (small weights would otherwise never take the second in operation (5)).  The automatic choices are what
+    the full-size tests run."""
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     binding.load_library()          # raises if the HIP library is not built: no fallback
-    binding.lora_set_row_tile(request.param)
+    binding.lora_set_row_tile(request.param[0])
+    binding.lora_set_slab_lookahead(request.param[1])
     yield
     binding.lora_set_row_tile(0)
+    binding.lora_set_slab_lookahead(0)
 
 
 @pytest.mark.parametrize("M,K,p,seed", [(256, 1024, 0.1, 0x25100206), (37, 130, 0.5, 0), (5, 7, 0.05, 1),

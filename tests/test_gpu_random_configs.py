@@ -85,6 +85,34 @@ def test_kernel_heights_agree(lens, r, ranks):
             assert rel_err(a, f64(b)) <= 1e-5, name
 
 
+@pytest.mark.parametrize("M,K,N,r,lens", [(704, 64, 320, 16, (704,)), (512, 128, 576, 32, (192, 320)), (600, 1152, 448, 64, (600,)),
+                                           (384, 2112, 256, 16, (100, 284)), (320, 256, 64, 16, (320,)), (448, 192, 128, 32, (64, 384))])
+def test_slab_lookahead_settings_agree(M, K, N, r, lens):
+    """The GEMMs copy their operand slabs one or two slabs ahead of the matrix work; the contraction order is the
+    same, so every output is the same bits under either setting and under the automatic choice, for both tile
+    heights - also for contractions of one and two slabs, where the pipelines differ most."""
+    L = workloads.custom_layer(M, K, N, r, 1.5, 0.2, seg_lens=lens, cfg=41)
+    Xg, Wg, Ag, Bg, dYg = (t.cuda() for t in workloads.make_inputs(L))
+    s, p = [1.0 + 0.5 * g for g in range(L.G)], [0.1 * (g + 1) for g in range(L.G)]
+    try:
+        for rows in (128, 256):
+            binding.lora_set_row_tile(rows)
+            outs = []
+            for ahead in (0, 1, 2):
+                print(f"lookahead M={M} K={K} N={N} r={r} lens={lens} rows={rows} ahead={ahead}", flush=True)
+                binding.lora_set_slab_lookahead(ahead)
+                Y, S = binding.multi_lora_fwd(Xg, Wg, Ag, Bg, L.seg_offsets, s, p, L.seeds)
+                dX, dA, dB = binding.multi_lora_bwd(Xg, Wg, Ag, Bg, S, dYg, L.seg_offsets, s, p, L.seeds)
+                torch.cuda.synchronize()
+                outs.append((Y, S, dX, dA, dB))
+            for other in outs[1:]:
+                for a, b, name in zip(outs[0], other, ("Y", "S", "dX", "dA", "dB")):
+                    assert torch.equal(a, b), (name, rows)
+    finally:
+        binding.lora_set_row_tile(0)
+        binding.lora_set_slab_lookahead(0)
+
+
 def test_row_tile_knob_is_read_once_per_call():
     """Another thread flips the kernel-height knob while backward calls are in flight: every call must
     still pair each streaming launch with a finalize launch of the same panel height, i.e. return one
