@@ -16,6 +16,7 @@
 // which it reads from LDS with transposing loads so that no transposed copy of the frozen weight is
 // ever kept.
 #include <atomic>
+#include <type_traits>
 
 #include "lf_device.h"
 #include "lf_internal.h"
@@ -922,20 +923,28 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dx_kernel(DxGemmArgs p) {
         const SlabLanes ss = row_slab_lanes<2 * MB>(rr, rt.rows, rr >> 3), sa = col_slab_lanes(p.K, rr, cols_valid);
         pp.src_tok = (const char*)dSt - kCopyBias;
         pp.src_out = (const char*)At - kCopyBias;
-        // step nk - D brings the LoRA slab pair; with D = 2 the last step brings nothing
-#pragma unroll 1
-        for (; kt < nk; ++kt) {
-            const bool bring = LORA && kt == nk - D, last = kt == nk - 1;
+        // step nk - D brings the LoRA slab pair; with D = 2 the last step brings nothing.  Each of the two steps is
+        // its own call with constant flags (no test per read or copy inside)
+        auto tail_step = [&](auto bring, auto read_next) {
             if constexpr (LORA) {
-                // one code path for these steps whatever kt is (two would have to merge all the accumulators):
+                // one code path for such a step whatever kt is (two would have to merge all the accumulators):
                 // past the 32nd step the hash pieces still run, on a step number that is never flushed
                 const bool forming = kt < FLAG_STEPS;
                 if (forming) keep_step_begin(kt);
-                slab_step<true, MB, CM>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sa, bring, !last, ks);
+                slab_step<true, MB, CM>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sa, LORA && bring(), read_next(), ks);
                 if (forming) keep_step_end(kt);
             } else {
-                slab_step<true, MB, CM>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sa, bring, !last, none);
+                slab_step<true, MB, CM>(acc, f, smem + tok_org, smem + out_org, corg, fl, pp, ss, sa, false, read_next(), none);
             }
+            ++kt;
+        };
+        using T = std::true_type;
+        using F = std::false_type;
+        if constexpr (D == 2) {
+            if (nk > 1) tail_step(T{}, T{});
+            tail_step(F{}, F{});
+        } else {
+            tail_step(T{}, F{});
         }
     }
     if constexpr (LORA) {
