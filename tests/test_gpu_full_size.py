@@ -50,6 +50,24 @@ def test_config_parity(cfg, li, zero_w):
     _check_layer(workloads.CONFIGS[cfg][li], li, zero_w)
 
 
+@pytest.mark.parametrize("cfg,li", [("c2", 0), ("c4", 0), ("c3", 2)], ids=lambda v: str(v))
+def test_slab_lookahead_settings_agree_at_full_size(cfg, li):
+    """The GEMMs' copies one and two slabs ahead (each launch picks one by itself: see test_config_parity for that
+    choice against the oracle) give the same bits at full size, also on the mixed tiles of c4."""
+    L = workloads.CONFIGS[cfg][li]
+    inp = workloads.make_inputs(L, layer_index=li)
+    outs = []
+    try:
+        for ahead in (1, 2):
+            print(f"full-size lookahead {L.name} ahead={ahead}", flush=True)
+            binding.lora_set_slab_lookahead(ahead)
+            outs.append(run_gpu(L, *inp))
+    finally:
+        binding.lora_set_slab_lookahead(0)
+    for name in ("Y", "S", "dX", "dA", "dB"):
+        assert torch.equal(outs[0][name], outs[1][name]), name
+
+
 def test_mid_size_parity():
     """4096 tokens at K = N = 4096 in three segments: the size at which the streaming reductions run
     128-row panels (256-row ones would leave half the compute units without a workgroup)."""
